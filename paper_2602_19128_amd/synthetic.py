@@ -1,0 +1,180 @@
+"""Seeded synthetic workloads for the fused MoE forward.
+
+This module only draws random tensors and stores them in the dtypes the layer
+consumes.  It holds none of the layer's arithmetic: no routing, no GEMM, no
+activation.  The one numeric step here is the block quantisation that turns
+generated values into the fp8 payload + fp32 scales an fp8 workload *arrives*
+with (inputs are quantised before the layer runs, never inside it).
+
+Shapes follow the MoE operator the paper analyses (Sec. 4.5: DeepSeek-V3 style,
+256 experts, top-8, hidden size 7168) plus a Mixtral-shaped and a tiny case.
+The paper measured on captured serving traces that are not available; these
+tensors stand in for them.
+
+Every tensor has its own generator stream derived from (seed, tensor id), so a
+tensor's values do not depend on which other tensors were generated, or in what
+order.  Values depend on the device the generator runs on (CPU and GPU use
+different generators); one test or benchmark always hands the *same* tensors to
+the kernels and to the checker.
+"""
+from __future__ import annotations
+
+import dataclasses
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import torch
+
+FP8_MAX = 448.0          # largest finite OCP e4m3fn magnitude
+QBLOCK = 128             # block edge of the fp8 scales
+
+
+@dataclass(frozen=True)
+class Workload:
+    """Problem statement of one MoE layer call (shapes + routing rule)."""
+    name: str
+    T: int                      # tokens
+    H: int                      # hidden size
+    I: int                      # expert intermediate size
+    E: int                      # experts
+    top_k: int
+    scoring: str = "softmax"    # "softmax" | "sigmoid"
+    n_group: int = 1            # >1: group-limited routing
+    topk_group: int = 1
+    group_score_topn: int = 2
+    routed_scale: float = 1.0
+    has_bias: bool = False
+    fp8: bool = False
+    hot_experts: int = 0        # skew variant: this many experts get +hot_bias
+    hot_bias: float = 0.0
+
+    def replace(self, **kw) -> "Workload":
+        return dataclasses.replace(self, **kw)
+
+
+_DSV3 = dict(H=7168, I=2048, E=256, top_k=8, scoring="sigmoid", n_group=8,
+             topk_group=4, group_score_topn=2, routed_scale=2.5, has_bias=True)
+
+WORKLOADS: Dict[str, Workload] = {
+    "tiny": Workload("tiny", T=16, H=256, I=128, E=8, top_k=2),
+    "mixtral_prefill": Workload("mixtral_prefill", T=512, H=4096, I=14336, E=8, top_k=2),
+    "dsv3_decode": Workload("dsv3_decode", T=64, **_DSV3),
+    "dsv3_prefill": Workload("dsv3_prefill", T=4096, **_DSV3),
+    "dsv3_prefill_skew": Workload("dsv3_prefill_skew", T=4096, hot_experts=16,
+                                  hot_bias=0.5, **_DSV3),
+    "fp8_prefill": Workload("fp8_prefill", T=1024, fp8=True, **_DSV3),
+}
+
+# tensor ids for the per-tensor generator streams
+_TID = {"x": 1, "router_w": 2, "bias": 3, "w1": 4, "w2": 5}
+
+
+def _gen(seed: int, tid: int, device) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(seed * 1_000_003 + tid * 7919 + 12345)
+    return g
+
+
+def _normal(shape, std: float, g: torch.Generator, device) -> torch.Tensor:
+    return torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std
+
+
+def hot_expert_ids(wl: Workload):
+    """Skew variant: the first `hot_experts / n_group` experts of every group."""
+    if wl.hot_experts <= 0:
+        return []
+    per = max(1, wl.hot_experts // max(1, wl.n_group))
+    gsz = wl.E // max(1, wl.n_group)
+    ids = []
+    for g in range(max(1, wl.n_group)):
+        ids.extend(g * gsz + j for j in range(per))
+    return ids[: wl.hot_experts]
+
+
+def quantize_rows_1x128(v: torch.Tensor):
+    """[R, K] fp32 -> (fp8 e4m3fn payload [R, K], fp32 scale [R, K/128]).
+
+    scale = amax(block) / 448 (1 if the block is all zero); payload = v / scale
+    rounded to nearest-even by the dtype conversion, clamped to +-448 first.
+    """
+    R, K = v.shape
+    assert K % QBLOCK == 0
+    b = v.reshape(R, K // QBLOCK, QBLOCK)
+    amax = b.abs().amax(dim=-1)
+    scale = torch.where(amax > 0, amax / FP8_MAX, torch.ones_like(amax))
+    q = (b / scale.unsqueeze(-1)).clamp_(-FP8_MAX, FP8_MAX).to(torch.float8_e4m3fn)
+    return q.reshape(R, K).contiguous(), scale.contiguous()
+
+
+def quantize_blocks_128x128(v: torch.Tensor):
+    """[N, K] fp32 -> (fp8 payload [N, K], fp32 scale [N/128, K/128])."""
+    N, K = v.shape
+    assert N % QBLOCK == 0 and K % QBLOCK == 0
+    b = v.reshape(N // QBLOCK, QBLOCK, K // QBLOCK, QBLOCK)
+    amax = b.abs().amax(dim=(1, 3))
+    scale = torch.where(amax > 0, amax / FP8_MAX, torch.ones_like(amax))
+    q = (b / scale[:, None, :, None]).clamp_(-FP8_MAX, FP8_MAX).to(torch.float8_e4m3fn)
+    return q.reshape(N, K).contiguous(), scale.contiguous()
+
+
+@dataclass
+class MoEInputs:
+    wl: Workload
+    x: torch.Tensor                       # [T,H] bf16, or fp8 e4m3fn when wl.fp8
+    router_w: torch.Tensor                # [E,H] fp32
+    bias: Optional[torch.Tensor]          # [E] fp32 or None
+    w1: torch.Tensor                      # [E,2I,H] bf16 / fp8 ; rows [0,I) gate, [I,2I) up
+    w2: torch.Tensor                      # [E,H,I]  bf16 / fp8
+    x_scale: Optional[torch.Tensor] = None    # [T,H/128] fp32
+    w1_scale: Optional[torch.Tensor] = None   # [E,2I/128,H/128] fp32
+    w2_scale: Optional[torch.Tensor] = None   # [E,H/128,I/128] fp32
+
+    def to(self, device) -> "MoEInputs":
+        mv = lambda t: None if t is None else t.to(device)
+        return MoEInputs(self.wl, mv(self.x), mv(self.router_w), mv(self.bias), mv(self.w1),
+                         mv(self.w2), mv(self.x_scale), mv(self.w1_scale), mv(self.w2_scale))
+
+
+def make_inputs(wl: Workload, seed: int = 0, device="cpu") -> MoEInputs:
+    """Draw one workload's tensors.
+
+    hidden ~ N(0,1); router W ~ N(0,1/H) fp32; expert weights ~ N(0,1/fan_in);
+    bias ~ U(-0.1,0.1) (+hot_bias on the hot experts).  bf16 workloads round to
+    bf16; fp8 workloads block-quantise (1x128 activations, 128x128 weights).
+    Expert weights are drawn one expert at a time to bound the fp32 temporaries.
+    """
+    dev = torch.device(device)
+    T, H, I, E = wl.T, wl.H, wl.I, wl.E
+    x32 = _normal((T, H), 1.0, _gen(seed, _TID["x"], dev), dev)
+    router_w = _normal((E, H), H ** -0.5, _gen(seed, _TID["router_w"], dev), dev)
+    bias = None
+    if wl.has_bias:
+        gb = _gen(seed, _TID["bias"], dev)
+        bias = (torch.rand((E,), generator=gb, device=dev, dtype=torch.float32) * 0.2 - 0.1)
+        hot = hot_expert_ids(wl)
+        if hot:
+            bias[torch.tensor(hot, device=dev)] += wl.hot_bias
+    wdt = torch.float8_e4m3fn if wl.fp8 else torch.bfloat16
+    w1 = torch.empty((E, 2 * I, H), dtype=wdt, device=dev)
+    w2 = torch.empty((E, H, I), dtype=wdt, device=dev)
+    w1_scale = w2_scale = x_scale = None
+    if wl.fp8:
+        w1_scale = torch.empty((E, 2 * I // QBLOCK, H // QBLOCK), dtype=torch.float32, device=dev)
+        w2_scale = torch.empty((E, H // QBLOCK, I // QBLOCK), dtype=torch.float32, device=dev)
+    g1 = _gen(seed, _TID["w1"], dev)
+    g2 = _gen(seed, _TID["w2"], dev)
+    for e in range(E):
+        a = _normal((2 * I, H), H ** -0.5, g1, dev)
+        b = _normal((H, I), I ** -0.5, g2, dev)
+        if wl.fp8:
+            w1[e], w1_scale[e] = quantize_blocks_128x128(a)
+            w2[e], w2_scale[e] = quantize_blocks_128x128(b)
+        else:
+            w1[e] = a.to(torch.bfloat16)
+            w2[e] = b.to(torch.bfloat16)
+        del a, b
+    if wl.fp8:
+        x, x_scale = quantize_rows_1x128(x32)
+    else:
+        x = x32.to(torch.bfloat16)
+    return MoEInputs(wl, x, router_w, bias, w1, w2, x_scale, w1_scale, w2_scale)
