@@ -1,0 +1,163 @@
+/*
+ * Fused Mixture-of-Experts layer forward for AMD Instinct MI355X (gfx950).
+ *
+ * The operator is the MoE layer the paper analyses in Sec. 4.5 ("Kernel
+ * Analysis: FP8 MoE Kernel"): every token scores all experts and keeps the top-k;
+ * the chosen experts run a gate and an up projection combined through SiLU, then a
+ * down projection.  The pipeline follows the one the paper credits for the fast
+ * kernel (Sec. 4.5, "Expert FFN computation"): (1) routing, (2) a sort-scatter
+ * that places each expert's tokens contiguously, (3) tensor-core expert GEMMs,
+ * with experts that received no token skipped; a weighted sum over the k experts
+ * of a token finishes the layer.
+ *
+ * Conventions for every entry point
+ *   - C ABI, plain pointers and sizes.  Unless marked HOST, a pointer is a DEVICE
+ *     pointer owned by the caller; tensors are contiguous, row-major, with the
+ *     shape written beside them, and 16-byte aligned.
+ *   - `stream` is the caller's hipStream_t (passed as void*; NULL = default
+ *     stream).  Calls only enqueue work: no allocation, no free, no host
+ *     synchronisation, no device-to-host copy happens inside the library.
+ *   - Same inputs give bit-identical outputs (no floating-point atomics anywhere).
+ *   - Return value: MOE_OK or a negative error code; nothing is enqueued when an
+ *     argument check fails.
+ *   - Shapes: H and I multiples of 64 (128 for fp8), E <= 512, top_k <= min(E,64).
+ *     Group-limited routing needs E % n_group == 0, a power-of-two number of
+ *     lanes per group (see moe_route) and top_k <= topk_group * E / n_group.
+ *   - Notation: T tokens, H hidden size, I expert intermediate size, E experts,
+ *     k = top_k, P = T*k (token, slot) pairs, pair id p = t*k + j.
+ */
+#ifndef MOE_H
+#define MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID = -1,       /* null pointer / inconsistent argument */
+    MOE_ERR_UNSUPPORTED = -2,   /* shape or dtype combination the kernels do not cover */
+    MOE_ERR_WORKSPACE = -3,     /* workspace too small */
+    MOE_ERR_HIP = -4            /* a launch failed; see moe_last_hip_error() */
+};
+
+enum { MOE_SCORE_SOFTMAX = 0, MOE_SCORE_SIGMOID = 1 };
+enum { MOE_DTYPE_BF16 = 0, MOE_DTYPE_FP8_E4M3 = 1 };
+
+/* Problem statement of one layer call (plain data, passed from HOST memory). */
+typedef struct moe_config {
+    int32_t T, H, I, E, top_k;
+    int32_t scoring;            /* MOE_SCORE_SOFTMAX: s = softmax(z), choice key c = s
+                                   MOE_SCORE_SIGMOID: s = sigmoid(z), c = s + bias      */
+    int32_t renormalize;        /* divide the k weights by their sum */
+    int32_t n_group;            /* <= 1: no group limiting.  Otherwise experts form n_group
+                                   contiguous blocks, a block scores the sum of its
+                                   group_score_topn largest keys, and only experts of the
+                                   topk_group best blocks may be chosen */
+    int32_t topk_group;
+    int32_t group_score_topn;
+    int32_t dtype;              /* payload type of x, w1, w2 (and of the act buffer) */
+    float   routed_scale;       /* final factor on the k weights */
+} moe_config;
+
+/* Row count of one tile of the grouped GEMMs for this problem (the height the
+ * tile list produced by moe_permute is cut to), and the capacity, in tiles, the
+ * caller must give the tile list. */
+int32_t moe_tile_rows(const moe_config *cfg);
+int32_t moe_max_tiles(const moe_config *cfg);
+
+/* One tile-list record: rows [row0, row0+rows) of the expert-sorted order all
+ * belong to `expert`; `first` is the index of that expert's first record and
+ * `count` how many records the expert has. */
+typedef struct moe_tile {
+    int32_t expert, row0, rows, first, count, pad0, pad1, pad2;
+} moe_tile;
+
+/* Bytes of device scratch moe_route / moe_forward need for this problem. */
+size_t moe_route_workspace_size(const moe_config *cfg);
+size_t moe_workspace_size(const moe_config *cfg);
+
+/*
+ * Routing (paper Sec. 4.5 "Routing": score all experts per token, keep the top-k).
+ * Logits z[t,e] = sum_h x[t,h] * router_w[e,h] in fp32, then the scoring rule of
+ * cfg; one wavefront per token selects the k experts with cross-lane exchanges.
+ *   x         [T,H] bf16, or fp8 e4m3 with x_scale [T,H/128] fp32 (else x_scale NULL)
+ *   router_w  [E,H] fp32;  bias [E] fp32 or NULL (added to the choice key only)
+ *   ids_out   [T,k] int32, experts in descending key order, equal keys -> lower index
+ *   w_out     [T,k] fp32, w = s[id] (/ sum over the k if renormalize) * routed_scale
+ *   workspace device scratch of at least moe_route_workspace_size(cfg) bytes
+ * Non-finite inputs give unspecified but in-range ids.
+ */
+int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+              const float *bias, int32_t *ids_out, float *w_out,
+              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Sort-scatter (paper Sec. 4.5: reorder tokens by expert into contiguous memory).
+ * A stable counting sort of the P pairs by expert id:
+ *   ids          [P] int32 (= the [T,k] routing result); ids outside [0,E) drop the pair
+ *   offsets_out  [E+1] int32, first sorted row of each expert; offsets[E] = kept pairs
+ *   sorted_pair_out [P] int32, pair stored at each sorted row (ascending p inside an expert)
+ *   inv_out      [P] int32, sorted row of each pair (-1 for a dropped pair)
+ *   tiles_out    [moe_max_tiles(cfg)] records cut at moe_tile_rows(cfg) rows, experts in
+ *                ascending order, none for an expert without tokens (such experts cost
+ *                nothing downstream); ntiles_out [1] int32 = records written
+ */
+int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
+                int32_t *sorted_pair_out, int32_t *inv_out, moe_tile *tiles_out,
+                int32_t *ntiles_out, void *stream);
+
+/*
+ * Gate/up grouped GEMM with fused SiLU gating (paper Sec. 4.5: "up" and "gate"
+ * projection combined via SiLU, on matrix cores with double-buffered tiles).
+ * For sorted row r of expert e holding pair p (token t = p / k):
+ *   g = x[t,:] . w1[e,i,:],  u = x[t,:] . w1[e,I+i,:],  act[r,i] = g*sigmoid(g)*u
+ *   w1 [E,2I,H] (rows [0,I) gate, [I,2I) up), fp32 accumulation.
+ *   bf16: act_out [P,I] bf16, scales NULL.
+ *   fp8 : w1_scale [E,2I/128,H/128], x_scale [T,H/128]; act_out [P,I] fp8 e4m3 and
+ *         act_scale_out [P,I/128] fp32 (act re-quantised per 1x128 block, scale = amax/448).
+ */
+int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x_scale,
+                            const void *w1, const float *w1_scale, const int32_t *sorted_pair,
+                            const moe_tile *tiles, const int32_t *ntiles,
+                            void *act_out, float *act_scale_out, void *stream);
+
+/*
+ * Down grouped GEMM (paper Sec. 4.5: "then a down-projection"):
+ *   y[r,h] = act[r,:] . w2[e,h,:],  w2 [E,H,I], fp32 accumulation, y_out [P,H] bf16.
+ *   fp8: act_scale [P,I/128], w2_scale [E,H/128,I/128]; else NULL.
+ */
+int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *act_scale,
+                          const void *w2, const float *w2_scale, const moe_tile *tiles,
+                          const int32_t *ntiles, void *y_out, void *stream);
+
+/*
+ * Weighted combine: out[t,:] = sum_{j<k} w[t,j] * y[inv[t*k+j],:], summed in slot
+ * order in fp32 (no atomics), rounded to bf16 (nearest-even).  Dropped pairs
+ * (inv < 0) contribute nothing.
+ *   y [P,H] bf16, w [T,k] fp32, inv [P] int32, out [T,H] bf16.
+ */
+int moe_combine(const moe_config *cfg, const void *y, const float *w, const int32_t *inv,
+                void *out, void *stream);
+
+/*
+ * The whole layer: the five steps above enqueued back to back on `stream`,
+ * intermediates in `workspace` (>= moe_workspace_size(cfg) bytes, 256-byte aligned).
+ * bias / *_scale may be NULL as described per step.  out [T,H] bf16.
+ */
+int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+                const float *bias, const void *w1, const float *w1_scale, const void *w2,
+                const float *w2_scale, void *out, void *workspace, size_t workspace_bytes,
+                void *stream);
+
+/* Text for an error code; the hipError_t of the last failed launch on this thread. */
+const char *moe_error_string(int code);
+int moe_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H */

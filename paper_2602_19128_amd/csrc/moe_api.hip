@@ -1,0 +1,208 @@
+// C ABI of the MoE library: argument checks, workspace carving, step sequencing.
+#include "moe_internal.hpp"
+
+namespace moe {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+namespace {
+
+int route_epl(int E) { return E <= 64 ? 1 : E <= 128 ? 2 : E <= 256 ? 4 : 8; }
+bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int validate(const moe_config *c)
+{
+    if (c == nullptr) return MOE_ERR_INVALID;
+    if (c->T < 0 || c->H <= 0 || c->I <= 0 || c->E <= 0 || c->top_k <= 0) return MOE_ERR_INVALID;
+    if (c->top_k > c->E) return MOE_ERR_INVALID;
+    if (c->scoring != MOE_SCORE_SOFTMAX && c->scoring != MOE_SCORE_SIGMOID) return MOE_ERR_INVALID;
+    if (c->dtype != MOE_DTYPE_BF16 && c->dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_INVALID;
+    if (c->E > kMaxExperts || c->top_k > kMaxTopK) return MOE_ERR_UNSUPPORTED;
+    if (c->H % 64 != 0 || c->I % 64 != 0) return MOE_ERR_UNSUPPORTED;
+    if (c->dtype == MOE_DTYPE_FP8_E4M3 && (c->H % kQBlock != 0 || c->I % kQBlock != 0)) return MOE_ERR_UNSUPPORTED;
+    if ((long long)c->T * c->top_k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
+    if (c->n_group > 1) {
+        if (c->E % c->n_group != 0) return MOE_ERR_INVALID;
+        const int gsz = c->E / c->n_group;
+        if (c->topk_group < 1 || c->topk_group > c->n_group) return MOE_ERR_INVALID;
+        if (c->group_score_topn < 1 || c->group_score_topn > gsz) return MOE_ERR_INVALID;
+        if (c->top_k > c->topk_group * gsz) return MOE_ERR_INVALID;
+        const int epl = route_epl(c->E);
+        if (gsz % epl != 0 || !is_pow2(gsz / epl)) return MOE_ERR_UNSUPPORTED;
+    }
+    return MOE_OK;
+}
+
+int tile_rows_for(const moe_config &c)
+{
+    const long long pairs = (long long)c.T * c.top_k;
+    const long long avg = pairs / c.E;
+    return avg >= 96 ? 128 : avg >= 40 ? 64 : 32;
+}
+
+int max_tiles_for(const moe_config &c)
+{
+    const int P = c.T * c.top_k;
+    return ceil_div(P, tile_rows_for(c)) + (P < c.E ? P : c.E);
+}
+
+// Workspace sections of moe_forward, in order, each 256-byte aligned.
+struct Layout {
+    size_t route, ids, w, offsets, sorted_pair, inv, tiles, ntiles, act, act_scale, y, total;
+};
+
+Layout layout_for(const moe_config &c)
+{
+    const size_t P = (size_t)c.T * c.top_k;
+    const size_t act_elem = c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
+    Layout l;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off += align_up(bytes ? bytes : 1, 256); return at; };
+    l.route = take(route_workspace_bytes(c));
+    l.ids = take(P * sizeof(int32_t));
+    l.w = take(P * sizeof(float));
+    l.offsets = take(((size_t)c.E + 1) * sizeof(int32_t));
+    l.sorted_pair = take(P * sizeof(int32_t));
+    l.inv = take(P * sizeof(int32_t));
+    l.tiles = take((size_t)max_tiles_for(c) * sizeof(moe_tile));
+    l.ntiles = take(sizeof(int32_t));
+    l.act = take(P * c.I * act_elem);
+    l.act_scale = take(c.dtype == MOE_DTYPE_FP8_E4M3 ? P * (c.I / kQBlock) * sizeof(float) : 0);
+    l.y = take(P * c.H * 2);
+    l.total = off;
+    return l;
+}
+
+bool fp8(const moe_config *c) { return c->dtype == MOE_DTYPE_FP8_E4M3; }
+
+}  // namespace
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+int32_t moe_tile_rows(const moe_config *cfg) { return validate(cfg) == MOE_OK ? tile_rows_for(*cfg) : 0; }
+int32_t moe_max_tiles(const moe_config *cfg) { return validate(cfg) == MOE_OK ? max_tiles_for(*cfg) : 0; }
+
+size_t moe_route_workspace_size(const moe_config *cfg)
+{
+    return validate(cfg) == MOE_OK ? route_workspace_bytes(*cfg) : 0;
+}
+
+size_t moe_workspace_size(const moe_config *cfg) { return validate(cfg) == MOE_OK ? layout_for(*cfg).total : 0; }
+
+int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+              const float *bias, int32_t *ids_out, float *w_out, void *workspace, size_t workspace_bytes,
+              void *stream)
+{
+    int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (cfg->T == 0) return MOE_OK;
+    if (!x || !router_w || !ids_out || !w_out || !workspace) return MOE_ERR_INVALID;
+    if (fp8(cfg) && !x_scale) return MOE_ERR_INVALID;
+    if (workspace_bytes < route_workspace_bytes(*cfg)) return MOE_ERR_WORKSPACE;
+    return launch_route(*cfg, x, x_scale, router_w, bias, ids_out, w_out, workspace, (hipStream_t)stream);
+}
+
+int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out, int32_t *sorted_pair_out,
+                int32_t *inv_out, moe_tile *tiles_out, int32_t *ntiles_out, void *stream)
+{
+    int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (!offsets_out || !ntiles_out) return MOE_ERR_INVALID;
+    if (cfg->T > 0 && (!ids || !sorted_pair_out || !inv_out || !tiles_out)) return MOE_ERR_INVALID;
+    return launch_permute(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), ids, offsets_out, sorted_pair_out,
+                          inv_out, tiles_out, ntiles_out, (hipStream_t)stream);
+}
+
+int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x_scale, const void *w1,
+                            const float *w1_scale, const int32_t *sorted_pair, const moe_tile *tiles,
+                            const int32_t *ntiles, void *act_out, float *act_scale_out, void *stream)
+{
+    int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (cfg->T == 0) return MOE_OK;
+    if (!x || !w1 || !sorted_pair || !tiles || !ntiles || !act_out) return MOE_ERR_INVALID;
+    if (fp8(cfg) && (!x_scale || !w1_scale || !act_scale_out)) return MOE_ERR_INVALID;
+    return launch_gemm_swiglu(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), x, x_scale, w1, w1_scale,
+                              sorted_pair, tiles, ntiles, act_out, act_scale_out, (hipStream_t)stream);
+}
+
+int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *act_scale, const void *w2,
+                          const float *w2_scale, const moe_tile *tiles, const int32_t *ntiles, void *y_out,
+                          void *stream)
+{
+    int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (cfg->T == 0) return MOE_OK;
+    if (!act || !w2 || !tiles || !ntiles || !y_out) return MOE_ERR_INVALID;
+    if (fp8(cfg) && (!act_scale || !w2_scale)) return MOE_ERR_INVALID;
+    return launch_gemm_down(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), act, act_scale, w2, w2_scale, tiles,
+                            ntiles, y_out, (hipStream_t)stream);
+}
+
+int moe_combine(const moe_config *cfg, const void *y, const float *w, const int32_t *inv, void *out,
+                void *stream)
+{
+    int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (cfg->T == 0) return MOE_OK;
+    if (!y || !w || !inv || !out) return MOE_ERR_INVALID;
+    return launch_combine(*cfg, y, w, inv, out, (hipStream_t)stream);
+}
+
+int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+                const float *bias, const void *w1, const float *w1_scale, const void *w2,
+                const float *w2_scale, void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (cfg->T == 0) return MOE_OK;
+    if (!x || !router_w || !w1 || !w2 || !out || !workspace) return MOE_ERR_INVALID;
+    if (fp8(cfg) && (!x_scale || !w1_scale || !w2_scale)) return MOE_ERR_INVALID;
+    if (((uintptr_t)workspace & 255u) != 0) return MOE_ERR_INVALID;
+    const Layout l = layout_for(*cfg);
+    if (workspace_bytes < l.total) return MOE_ERR_WORKSPACE;
+
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    int32_t *ids = reinterpret_cast<int32_t *>(ws + l.ids);
+    float *w = reinterpret_cast<float *>(ws + l.w);
+    int32_t *offsets = reinterpret_cast<int32_t *>(ws + l.offsets);
+    int32_t *sorted_pair = reinterpret_cast<int32_t *>(ws + l.sorted_pair);
+    int32_t *inv = reinterpret_cast<int32_t *>(ws + l.inv);
+    moe_tile *tiles = reinterpret_cast<moe_tile *>(ws + l.tiles);
+    int32_t *ntiles = reinterpret_cast<int32_t *>(ws + l.ntiles);
+    void *act = ws + l.act;
+    float *act_scale = fp8(cfg) ? reinterpret_cast<float *>(ws + l.act_scale) : nullptr;
+    void *y = ws + l.y;
+    hipStream_t s = (hipStream_t)stream;
+    const int tr = tile_rows_for(*cfg), mt = max_tiles_for(*cfg);
+
+    rc = launch_route(*cfg, x, x_scale, router_w, bias, ids, w, ws + l.route, s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_permute(*cfg, tr, mt, ids, offsets, sorted_pair, inv, tiles, ntiles, s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_gemm_swiglu(*cfg, tr, mt, x, x_scale, w1, w1_scale, sorted_pair, tiles, ntiles, act, act_scale, s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_gemm_down(*cfg, tr, mt, act, act_scale, w2, w2_scale, tiles, ntiles, y, s);
+    if (rc != MOE_OK) return rc;
+    return launch_combine(*cfg, y, w, inv, out, s);
+}
+
+const char *moe_error_string(int code)
+{
+    switch (code) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_INVALID: return "invalid argument";
+    case MOE_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case MOE_ERR_WORKSPACE: return "workspace too small";
+    case MOE_ERR_HIP: return "HIP launch failed";
+    default: return "unknown error";
+    }
+}
+
+int moe_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,55 @@
+// Weighted combine: out[t,:] = sum_j w[t,j] * y[inv[t*k+j],:].
+//
+// Each thread owns 8 consecutive hidden elements of one token and walks the token's
+// k expert rows in slot order, so the fp32 sum has one fixed order and needs no
+// atomics; the result is rounded once to bf16 (nearest-even).
+#include "moe_internal.hpp"
+
+namespace moe {
+namespace {
+
+__global__ __launch_bounds__(256) void combine_kernel(const uint16_t *__restrict__ y,
+                                                      const float *__restrict__ w,
+                                                      const int32_t *__restrict__ inv,
+                                                      uint16_t *__restrict__ out, int T, int H, int k)
+{
+    const int chunks = H / 8;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)T * chunks) return;
+    const int t = (int)(idx / chunks), h = (int)(idx % chunks) * 8;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int j = 0; j < k; ++j) {
+        const int row = inv[(size_t)t * k + j];
+        if (row < 0) continue;
+        const float wt = w[(size_t)t * k + j];
+        const uint4 raw = *reinterpret_cast<const uint4 *>(y + (size_t)row * H + h);
+        const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] = fmaf(wt, bf16_bits_to_f32(v[i] & 0xffffu), acc[2 * i]);
+            acc[2 * i + 1] = fmaf(wt, bf16_bits_to_f32(v[i] >> 16), acc[2 * i + 1]);
+        }
+    }
+    uint4 o;
+    o.x = pack_bf16x2(acc[0], acc[1]);
+    o.y = pack_bf16x2(acc[2], acc[3]);
+    o.z = pack_bf16x2(acc[4], acc[5]);
+    o.w = pack_bf16x2(acc[6], acc[7]);
+    *reinterpret_cast<uint4 *>(out + (size_t)t * H + h) = o;
+}
+
+}  // namespace
+
+int launch_combine(const moe_config &c, const void *y, const float *w, const int32_t *inv, void *out,
+                   hipStream_t s)
+{
+    const long long work = (long long)c.T * (c.H / 8);
+    const unsigned blocks = (unsigned)((work + 255) / 256);
+    hipLaunchKernelGGL(combine_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const uint16_t *>(y), w, inv,
+                       static_cast<uint16_t *>(out), c.T, c.H, c.top_k);
+    return check_launch();
+}
+
+}  // namespace moe

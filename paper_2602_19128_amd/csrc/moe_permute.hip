@@ -1,0 +1,140 @@
+// Sort-scatter (paper Sec. 4.5: tokens reordered by expert into contiguous memory).
+//
+// One workgroup of 16 wavefronts does a stable counting sort of the P (token, slot)
+// pairs by expert id entirely in LDS: per-wavefront histograms, a prefix scan over
+// experts, then each wavefront walks its contiguous slice of pairs in order and
+// ranks equal experts inside a 64-pair batch with ballots.  The same kernel cuts
+// every non-empty expert segment into row tiles for the grouped GEMMs; experts
+// without tokens get no tile and therefore cost nothing downstream.
+#include "moe_internal.hpp"
+
+namespace moe {
+namespace {
+
+constexpr int PM_THREADS = 1024;
+constexpr int PM_WAVES = PM_THREADS / kWave;
+
+// Inclusive scan of n <= kMaxExperts ints held in LDS (Hillis-Steele, all threads sync).
+__device__ inline void block_inclusive_scan(int *a, int *b, int n, int tid)
+{
+    int *src = a, *dst = b;
+    for (int off = 1; off < n; off <<= 1) {
+        if (tid < n) dst[tid] = src[tid] + (tid >= off ? src[tid - off] : 0);
+        __syncthreads();
+        int *tmp = src; src = dst; dst = tmp;
+    }
+    if (src != a) {
+        if (tid < n) a[tid] = src[tid];
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__restrict__ ids, int P, int E,
+                                                             int tile_rows, int max_tiles,
+                                                             int32_t *__restrict__ offsets,
+                                                             int32_t *__restrict__ sorted_pair,
+                                                             int32_t *__restrict__ inv,
+                                                             moe_tile *__restrict__ tiles,
+                                                             int32_t *__restrict__ ntiles)
+{
+    extern __shared__ int lds[];
+    int *wcount = lds;                         // [PM_WAVES][E]  per-wavefront counts -> write cursors
+    int *scan_a = wcount + PM_WAVES * E;       // [E]
+    int *scan_b = scan_a + E;                  // [E]
+    int *first_row = scan_b + E;               // [E+1] exclusive offsets
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int per_wave = ceil_div(ceil_div(P, PM_WAVES), kWave) * kWave;
+    const int p_beg = min(P, wave * per_wave), p_end = min(P, p_beg + per_wave);
+
+    for (int i = tid; i < PM_WAVES * E; i += PM_THREADS) wcount[i] = 0;
+    __syncthreads();
+
+    // pass 1: histogram of this wavefront's slice (integer LDS adds: order-independent)
+    for (int p = p_beg + lane; p < p_end; p += kWave) {
+        const int e = ids[p];
+        if (e >= 0 && e < E) atomicAdd(&wcount[wave * E + e], 1);
+    }
+    __syncthreads();
+
+    // rows per expert -> exclusive offsets
+    int total = 0;
+    if (tid < E)
+        for (int wv = 0; wv < PM_WAVES; ++wv) total += wcount[wv * E + tid];
+    if (tid < E) scan_a[tid] = total;
+    __syncthreads();
+    block_inclusive_scan(scan_a, scan_b, E, tid);
+    if (tid < E) {
+        const int excl = scan_a[tid] - total;
+        first_row[tid] = excl;
+        offsets[tid] = excl;
+        int run = excl;                        // turn counts into per-wavefront write cursors
+        for (int wv = 0; wv < PM_WAVES; ++wv) {
+            const int c = wcount[wv * E + tid];
+            wcount[wv * E + tid] = run;
+            run += c;
+        }
+        if (tid == E - 1) { first_row[E] = scan_a[tid]; offsets[E] = scan_a[tid]; }
+    }
+    __syncthreads();
+
+    // tile list: expert e gets ceil(rows_e / tile_rows) records, experts in ascending order
+    const int my_tiles = (tid < E) ? ceil_div(total, tile_rows) : 0;
+    if (tid < E) scan_a[tid] = my_tiles;
+    __syncthreads();
+    block_inclusive_scan(scan_a, scan_b, E, tid);
+    if (tid < E) {
+        const int first = scan_a[tid] - my_tiles;
+        for (int i = 0; i < my_tiles && first + i < max_tiles; ++i) {
+            moe_tile rec;
+            rec.expert = tid;
+            rec.row0 = first_row[tid] + i * tile_rows;
+            rec.rows = min(tile_rows, total - i * tile_rows);
+            rec.first = first;
+            rec.count = my_tiles;
+            rec.pad0 = rec.pad1 = rec.pad2 = 0;
+            tiles[first + i] = rec;
+        }
+        if (tid == E - 1) *ntiles = min(scan_a[tid], max_tiles);
+    }
+
+    // pass 2: stable placement.  Batches of 64 consecutive pairs; inside a batch a pair's
+    // rank among equal experts is the number of lower lanes holding the same expert.
+    volatile int *cursor = wcount + wave * E;
+    const int ebits = 32 - __clz(max(E - 1, 1));
+    for (int base = p_beg; base < p_end; base += kWave) {
+        const int p = base + lane;
+        const int e = (p < p_end) ? ids[p] : -1;
+        const bool valid = e >= 0 && e < E;
+        unsigned long long same = __ballot(valid);
+        for (int b = 0; b < ebits; ++b) {
+            const unsigned long long m = __ballot((e >> b) & 1);
+            same &= ((e >> b) & 1) ? m : ~m;
+        }
+        const unsigned long long lower = (1ull << lane) - 1ull;
+        if (valid) {
+            const int rank = __popcll(same & lower);
+            const int row = cursor[e] + rank;
+            sorted_pair[row] = p;
+            inv[p] = row;
+            if (rank == 0) cursor[e] = cursor[e] + __popcll(same);   // one lane per expert advances it
+        } else if (p < p_end) {
+            inv[p] = -1;
+        }
+    }
+}
+
+}  // namespace
+
+int launch_permute(const moe_config &c, int tile_rows, int max_tiles, const int32_t *ids,
+                   int32_t *offsets, int32_t *sorted_pair, int32_t *inv, moe_tile *tiles,
+                   int32_t *ntiles, hipStream_t s)
+{
+    const int P = c.T * c.top_k;
+    const size_t lds = sizeof(int) * ((size_t)PM_WAVES * c.E + 3 * (size_t)c.E + 1);
+    hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PM_THREADS), lds, s, ids, P, c.E, tile_rows, max_tiles,
+                       offsets, sorted_pair, inv, tiles, ntiles);
+    return check_launch();
+}
+
+}  // namespace moe

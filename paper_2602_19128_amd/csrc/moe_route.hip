@@ -1,0 +1,335 @@
+// Routing (paper Sec. 4.5 "Routing"): score every expert for every token, keep the top-k.
+//
+// Two kernels:
+//   router_logits_kernel  z = x . router_w^T in fp32, LDS-tiled, split along H so that a
+//                         handful of decode tokens still fills the chip; partial sums go
+//                         to scratch and are added in a fixed order (deterministic).
+//   router_topk_kernel    one 64-lane wavefront per token: scoring rule, optional
+//                         group limiting, then k rounds of a cross-lane arg-max.
+#include "moe_internal.hpp"
+
+namespace moe {
+namespace {
+
+constexpr int RT_TM = 64;     // tokens per workgroup tile
+constexpr int RT_TN = 64;     // experts per workgroup tile
+constexpr int RT_BK = 32;     // hidden elements per LDS stage
+constexpr int RT_PAD = 4;
+constexpr int RT_MAX_SPLIT = 32;
+
+struct RouteGrid { int tiles_t, tiles_e, splits, k_per_split; };
+
+RouteGrid route_grid(const moe_config &c)
+{
+    RouteGrid g;
+    g.tiles_t = ceil_div(c.T, RT_TM);
+    g.tiles_e = ceil_div(c.E, RT_TN);
+    const int chunks = ceil_div(c.H, RT_BK);
+    int want = ceil_div(512, g.tiles_t * g.tiles_e);          // aim at >= 2 workgroups per CU
+    if (want > RT_MAX_SPLIT) want = RT_MAX_SPLIT;
+    if (want > chunks) want = chunks;
+    if (want < 1) want = 1;
+    g.k_per_split = ceil_div(chunks, want) * RT_BK;
+    g.splits = ceil_div(c.H, g.k_per_split);
+    return g;
+}
+
+// 8 consecutive hidden values of one token as fp32 (zero outside the tensor).
+template <bool FP8>
+__device__ inline void load_x8(const void *x, const float *x_scale, int T, int H, int t, int h, float v[8])
+{
+    if (t >= T || h >= H) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = 0.f;
+        return;
+    }
+    if constexpr (FP8) {
+        const uint2 raw = *reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(x) + (size_t)t * H + h);
+        const float sc = x_scale[(size_t)t * (H / kQBlock) + h / kQBlock];
+        v[0] = __builtin_amdgcn_cvt_f32_fp8(raw.x, 0) * sc;
+        v[1] = __builtin_amdgcn_cvt_f32_fp8(raw.x, 1) * sc;
+        v[2] = __builtin_amdgcn_cvt_f32_fp8(raw.x, 2) * sc;
+        v[3] = __builtin_amdgcn_cvt_f32_fp8(raw.x, 3) * sc;
+        v[4] = __builtin_amdgcn_cvt_f32_fp8(raw.y, 0) * sc;
+        v[5] = __builtin_amdgcn_cvt_f32_fp8(raw.y, 1) * sc;
+        v[6] = __builtin_amdgcn_cvt_f32_fp8(raw.y, 2) * sc;
+        v[7] = __builtin_amdgcn_cvt_f32_fp8(raw.y, 3) * sc;
+    } else {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(x) + (size_t)t * H + h);
+        v[0] = bf16_bits_to_f32(raw.x & 0xffffu); v[1] = bf16_bits_to_f32(raw.x >> 16);
+        v[2] = bf16_bits_to_f32(raw.y & 0xffffu); v[3] = bf16_bits_to_f32(raw.y >> 16);
+        v[4] = bf16_bits_to_f32(raw.z & 0xffffu); v[5] = bf16_bits_to_f32(raw.z >> 16);
+        v[6] = bf16_bits_to_f32(raw.w & 0xffffu); v[7] = bf16_bits_to_f32(raw.w >> 16);
+    }
+}
+
+template <bool FP8>
+__global__ __launch_bounds__(256) void router_logits_kernel(const void *__restrict__ x,
+                                                            const float *__restrict__ x_scale,
+                                                            const float *__restrict__ router_w,
+                                                            float *__restrict__ zpart, int T, int H, int E,
+                                                            int k_per_split)
+{
+    __shared__ float As[RT_BK][RT_TM + RT_PAD];
+    __shared__ float Bs[RT_BK][RT_TN + RT_PAD];
+    const int tid = threadIdx.x;
+    const int t0 = blockIdx.x * RT_TM, e0 = blockIdx.y * RT_TN;
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = min(H, kbeg + k_per_split);
+    const int lrow = tid >> 2, lk = (tid & 3) * 8;       // loader coordinates
+    const int ty = tid >> 4, tx = tid & 15;              // 4x4 outputs per thread
+
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    for (int k0 = kbeg; k0 < kend; k0 += RT_BK) {
+        float xv[8], wv[8];
+        load_x8<FP8>(x, x_scale, T, H, t0 + lrow, k0 + lk, xv);
+        if (e0 + lrow < E && k0 + lk < H) {
+            const float4 *src = reinterpret_cast<const float4 *>(router_w + (size_t)(e0 + lrow) * H + k0 + lk);
+            const float4 a = src[0], b = src[1];
+            wv[0] = a.x; wv[1] = a.y; wv[2] = a.z; wv[3] = a.w;
+            wv[4] = b.x; wv[5] = b.y; wv[6] = b.z; wv[7] = b.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) wv[j] = 0.f;
+        }
+        __syncthreads();                                  // previous stage fully consumed
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            As[lk + j][lrow] = xv[j];
+            Bs[lk + j][lrow] = wv[j];
+        }
+        __syncthreads();
+        // two-level summation: a short chain per stage, added to the running total
+        float part[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) part[i][j] = 0.f;
+#pragma unroll
+        for (int k = 0; k < RT_BK; ++k) {
+            const float4 a = *reinterpret_cast<const float4 *>(&As[k][ty * 4]);
+            const float4 b = *reinterpret_cast<const float4 *>(&Bs[k][tx * 4]);
+            const float av[4] = {a.x, a.y, a.z, a.w};
+            const float bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) part[i][j] = fmaf(av[i], bv[j], part[i][j]);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] += part[i][j];
+    }
+
+    float *dst = zpart + (size_t)blockIdx.z * T * E;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = t0 + ty * 4 + i;
+        if (t >= T) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = e0 + tx * 4 + j;
+            if (e < E) dst[(size_t)t * E + e] = acc[i][j];
+        }
+    }
+}
+
+// ---- cross-lane helpers -------------------------------------------------------
+
+// Monotone map fp32 -> uint32 (larger float <=> larger integer).
+__device__ inline uint32_t orderable(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// (key, expert) packed so that an unsigned max picks the larger key, then the lower index.
+__device__ inline unsigned long long pack_key(float c, int e)
+{
+    return ((unsigned long long)orderable(c) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)e);
+}
+
+__device__ inline unsigned long long shfl_xor_u64(unsigned long long v, int mask)
+{
+    const uint32_t lo = __shfl_xor((int)(uint32_t)v, mask, kWave);
+    const uint32_t hi = __shfl_xor((int)(uint32_t)(v >> 32), mask, kWave);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// max over aligned segments of `width` lanes (width = power of two <= 64)
+__device__ inline unsigned long long seg_max_u64(unsigned long long v, int width)
+{
+    for (int m = 1; m < width; m <<= 1) {
+        const unsigned long long o = shfl_xor_u64(v, m);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+__device__ inline float wave_max_f32(float v)
+{
+    for (int m = 1; m < kWave; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+    return v;
+}
+
+__device__ inline float wave_sum_f32(float v)
+{
+    for (int m = 1; m < kWave; m <<= 1) v += __shfl_xor(v, m, kWave);   // butterfly: same value on every lane
+    return v;
+}
+
+struct TopkParams {
+    int T, E, top_k, scoring, renormalize, n_group, topk_group, group_score_topn, splits;
+    float routed_scale;
+};
+
+// Lane l owns experts l*EPL .. l*EPL+EPL-1 (contiguous, so a group of experts is a run of lanes).
+template <int EPL>
+__global__ __launch_bounds__(256) void router_topk_kernel(const float *__restrict__ zpart,
+                                                          const float *__restrict__ bias,
+                                                          int32_t *__restrict__ ids, float *__restrict__ w,
+                                                          TopkParams p)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int t = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (t >= p.T) return;                                  // whole wave leaves together
+    const int E = p.E;
+
+    float z[EPL], s[EPL];
+    unsigned long long key[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        const int e = lane * EPL + i;
+        float acc = 0.f;
+        if (e < E)
+            for (int sp = 0; sp < p.splits; ++sp) acc += zpart[((size_t)sp * p.T + t) * E + e];
+        z[i] = acc;
+    }
+
+    if (p.scoring == MOE_SCORE_SOFTMAX) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) if (lane * EPL + i < E) m = fmaxf(m, z[i]);
+        m = wave_max_f32(m);
+        float den = 0.f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            s[i] = (lane * EPL + i < E) ? expf(z[i] - m) : 0.f;
+            den += s[i];
+        }
+        den = wave_sum_f32(den);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) s[i] = s[i] / den;
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) s[i] = 1.f / (1.f + expf(-z[i]));
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        const int e = lane * EPL + i;
+        const float c = s[i] + ((bias != nullptr && e < E) ? bias[e] : 0.f);
+        key[i] = (e < E) ? pack_key(c, e) : 0ull;          // 0 = not a candidate
+    }
+
+    // ---- group limiting ----------------------------------------------------
+    if (p.n_group > 1) {
+        const int gsz = E / p.n_group;
+        const int lpg = gsz / EPL;                         // lanes per group (power of two)
+        const int my_group = lane / lpg;
+        unsigned long long left[EPL];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) left[i] = key[i];
+        float gscore = 0.f;
+        for (int n = 0; n < p.group_score_topn; ++n) {
+            unsigned long long best = 0ull;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) best = left[i] > best ? left[i] : best;
+            best = seg_max_u64(best, lpg);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) if (left[i] == best) left[i] = 0ull;
+            // undo the order-preserving map to get the key value back
+            const uint32_t ob = (uint32_t)(best >> 32);
+            const uint32_t fb = (ob & 0x80000000u) ? (ob & 0x7fffffffu) : ~ob;
+            gscore += (best != 0ull) ? __uint_as_float(fb) : 0.f;
+        }
+        int rank = 0;
+        for (int g = 0; g < p.n_group; ++g) {
+            const float og = __shfl(gscore, g * lpg, kWave);
+            rank += (og > gscore) || (og == gscore && g < my_group);
+        }
+        const bool kept = my_group < p.n_group && rank < p.topk_group;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) if (!kept) key[i] = 0ull;
+    }
+
+    // ---- k rounds of wave-wide arg-max ----------------------------------------
+    int my_id = 0;
+    float my_s = 0.f;
+    for (int j = 0; j < p.top_k; ++j) {
+        unsigned long long best = 0ull;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) best = key[i] > best ? key[i] : best;
+        best = seg_max_u64(best, kWave);
+        int e = (int)(0xffffffffu - (uint32_t)best);
+        e = e < 0 ? 0 : (e >= E ? E - 1 : e);              // keeps ids in range whatever the inputs
+        float sel = 0.f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i)
+            if (lane * EPL + i == e) { sel = s[i]; key[i] = 0ull; }
+        sel = __shfl(sel, e / EPL, kWave);
+        if (lane == j) { my_id = e; my_s = sel; }
+    }
+    float sum = 0.f;
+    for (int j = 0; j < p.top_k; ++j) sum += __shfl(my_s, j, kWave);   // slot order
+    if (lane < p.top_k) {
+        float wt = my_s;
+        if (p.renormalize) wt = wt / sum;
+        wt *= p.routed_scale;
+        ids[(size_t)t * p.top_k + lane] = my_id;
+        w[(size_t)t * p.top_k + lane] = wt;
+    }
+}
+
+}  // namespace
+
+size_t route_workspace_bytes(const moe_config &c)
+{
+    const RouteGrid g = route_grid(c);
+    return align_up((size_t)g.splits * c.T * c.E * sizeof(float), 256);
+}
+
+int launch_route(const moe_config &c, const void *x, const float *x_scale, const float *router_w,
+                 const float *bias, int32_t *ids, float *w, void *ws, hipStream_t s)
+{
+    const RouteGrid g = route_grid(c);
+    float *zpart = static_cast<float *>(ws);
+    const dim3 grid(g.tiles_t, g.tiles_e, g.splits);
+    if (c.dtype == MOE_DTYPE_FP8_E4M3)
+        hipLaunchKernelGGL(router_logits_kernel<true>, grid, dim3(256), 0, s, x, x_scale, router_w, zpart,
+                           c.T, c.H, c.E, g.k_per_split);
+    else
+        hipLaunchKernelGGL(router_logits_kernel<false>, grid, dim3(256), 0, s, x, x_scale, router_w, zpart,
+                           c.T, c.H, c.E, g.k_per_split);
+    int rc = check_launch();
+    if (rc != MOE_OK) return rc;
+
+    TopkParams p{c.T, c.E, c.top_k, c.scoring, c.renormalize, c.n_group, c.topk_group,
+                 c.group_score_topn, g.splits, c.routed_scale};
+    const dim3 tgrid(ceil_div(c.T, 4));
+    const int epl = c.E <= 64 ? 1 : c.E <= 128 ? 2 : c.E <= 256 ? 4 : 8;
+    switch (epl) {
+    case 1: hipLaunchKernelGGL(router_topk_kernel<1>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
+    case 2: hipLaunchKernelGGL(router_topk_kernel<2>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
+    case 4: hipLaunchKernelGGL(router_topk_kernel<4>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
+    default: hipLaunchKernelGGL(router_topk_kernel<8>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
+    }
+    return check_launch();
+}
+
+}  // namespace moe

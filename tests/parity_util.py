@@ -1,0 +1,100 @@
+"""Shared comparison helpers of the GPU parity tests (GPU library vs CPU oracle)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import moe_oracle as orc
+
+# Tolerances of the layer output (bf16 path / fp8 path), relative to max|ref| and as
+# mean relative error sum|err| / sum|ref|.
+TOL_MAX = {False: 2e-2, True: 6e-2}
+TOL_MEAN = {False: 5e-3, True: 3e-2}
+TIE_MARGIN = 1e-6           # routing decisions closer than this may legitimately differ
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def err_stats(got: np.ndarray, ref: np.ndarray):
+    err = np.abs(got - ref)
+    peak = float(np.abs(ref).max()) if ref.size else 0.0
+    max_rel = float(err.max() / peak) if ref.size and peak > 0 else 0.0
+    mean_rel = float(err.sum() / np.abs(ref).sum()) if ref.size and np.abs(ref).sum() > 0 else 0.0
+    return max_rel, mean_rel
+
+
+def compare_routing(ids_gpu, w_gpu, ids_ref, w_ref, margin, routed_scale=1.0, n_experts=None, key_ref=None):
+    """Expert ids must match the oracle bit for bit, in order.  Two exceptions, both
+    counted and returned: a token whose decision margin in the oracle is below
+    TIE_MARGIN may pick a different expert set, and two chosen experts whose keys
+    are that close may swap slots (same set, weights equal per expert).
+    Weights must agree to fp32 accuracy.
+    Returns (tokens_with_other_set, tokens_with_swapped_slots, same_set_mask)."""
+    ids_gpu = ids_gpu.cpu().numpy()
+    w_gpu = w_gpu.cpu().numpy().astype(np.float64)
+    T, k = ids_ref.shape
+    atol = 2e-6 * max(1.0, routed_scale)
+    if n_experts is not None:
+        assert ((ids_gpu >= 0) & (ids_gpu < n_experts)).all(), "expert id out of range"
+    exact = (ids_gpu == ids_ref).all(axis=1)
+    same_set = np.array([sorted(ids_gpu[t]) == sorted(ids_ref[t]) for t in range(T)], dtype=bool)
+    for t in range(T):
+        assert len(set(ids_gpu[t].tolist())) == k, f"token {t}: experts not distinct"
+    bad = ~same_set & (margin >= TIE_MARGIN)
+    if bad.any():
+        t = int(np.nonzero(bad)[0][0])
+        raise AssertionError(f"{int(bad.sum())} tokens routed differently with margin >= {TIE_MARGIN}: "
+                             f"first t={t} gpu={ids_gpu[t]} ref={ids_ref[t]} margin={margin[t]}")
+    for t in np.nonzero(same_set & ~exact)[0]:
+        slot = {int(e): j for j, e in enumerate(ids_ref[t])}
+        perm = [slot[int(e)] for e in ids_gpu[t]]
+        np.testing.assert_allclose(w_gpu[t], w_ref[t][perm], rtol=2e-5, atol=atol)
+        if key_ref is not None:           # the experts that changed slot must have near-equal keys
+            moved = [int(ids_ref[t][j]) for j in range(k) if perm[j] != j]
+            spread = key_ref[t][moved].max() - key_ref[t][moved].min()
+            assert spread < 2 * TIE_MARGIN, f"token {t}: slots swapped between unequal experts"
+    if exact.any():
+        np.testing.assert_allclose(w_gpu[exact], w_ref[exact], rtol=2e-5, atol=atol)
+    return int((~same_set).sum()), int((same_set & ~exact).sum()), same_set
+
+
+def check_tiles(tiles, ntiles, offsets_ref, tile_rows):
+    """The tile list covers every non-empty expert segment exactly, in order."""
+    n = int(ntiles.cpu().item())
+    rec = tiles.cpu().numpy()[:n]
+    want = []
+    E = len(offsets_ref) - 1
+    for e in range(E):
+        lo, hi = int(offsets_ref[e]), int(offsets_ref[e + 1])
+        cnt = -(-(hi - lo) // tile_rows)
+        first = len(want)
+        for i in range(cnt):
+            r0 = lo + i * tile_rows
+            want.append([e, r0, min(tile_rows, hi - r0), first, cnt])
+    assert n == len(want), f"{n} tiles, expected {len(want)}"
+    if n:
+        assert np.array_equal(rec[:, :5], np.array(want, dtype=np.int32))
+    return n
+
+
+def choice_keys(p, z):
+    """Choice key of every expert from the oracle's logits (only used to judge slot swaps)."""
+    if p.scoring == "softmax":
+        s = np.exp(z - z.max(axis=1, keepdims=True))
+        s /= s.sum(axis=1, keepdims=True)
+    else:
+        s = 1.0 / (1.0 + np.exp(-z))
+    if p.bias is not None:
+        s = s + p._b.astype(np.float64)[None, :]
+    return s
+
+
+def oracle_all(inp):
+    """Oracle routing for every token + the permutation of that routing."""
+    p = orc.problem_from_inputs(inp)
+    z = orc.router_logits(p)
+    ids, w, margin = orc.route(p, z)
+    offsets, sorted_pair, inv = orc.permute(ids, p.E)
+    return p, ids, w, margin, offsets, sorted_pair, inv, choice_keys(p, z)

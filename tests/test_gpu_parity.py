@@ -1,0 +1,171 @@
+"""GPU parity: every step of the HIP path against the CPU oracle, through the C ABI.
+
+Small cases span several row tiles with ragged tails and exercise each tile
+height the library picks; the oracle runs them in full.  Staged steps are fed
+oracle-verified inputs so that one step's rounding cannot hide in the next.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as orc
+from paper_2602_19128_amd import binding as moe
+from paper_2602_19128_amd import synthetic as syn
+from parity_util import (TOL_MAX, TOL_MEAN, check_tiles, compare_routing, err_stats, f64, oracle_all)
+
+pytestmark = pytest.mark.gpu
+
+GROUPED = dict(scoring="sigmoid", has_bias=True, routed_scale=2.5, group_score_topn=2)
+
+CASES = {
+    # name: workload                                                        (tile height picked)
+    "tiny": syn.WORKLOADS["tiny"],                                                      # 32
+    "ragged64": syn.Workload("ragged64", T=203, H=256, I=192, E=8, top_k=2),            # 64
+    "ragged128": syn.Workload("ragged128", T=301, H=320, I=128, E=4, top_k=2),          # 128
+    "sparse32": syn.Workload("sparse32", T=33, H=256, I=128, E=64, top_k=6),            # 32, empty experts
+    "grouped": syn.Workload("grouped", T=70, H=256, I=128, E=16, top_k=4, n_group=4,
+                            topk_group=2, **GROUPED),
+    "dsv3_like": syn.Workload("dsv3_like", T=96, H=512, I=128, E=256, top_k=8, n_group=8,
+                              topk_group=4, **GROUPED),
+    "one_token": syn.Workload("one_token", T=1, H=128, I=64, E=8, top_k=3),
+    "one_expert": syn.Workload("one_expert", T=40, H=128, I=64, E=1, top_k=1),
+    "all_experts": syn.Workload("all_experts", T=24, H=128, I=64, E=4, top_k=4),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request):
+    wl = CASES[request.param]
+    print(f"\n[case] {wl}", flush=True)
+    cpu = syn.make_inputs(wl, seed=0)
+    return wl, cpu, cpu.to("cuda"), oracle_all(cpu)
+
+
+def test_route(case):
+    wl, cpu, gpu, (p, ids, w, margin, *_rest, keys) = case
+    cfg = moe.MoEConfig.from_workload(wl)
+    ids_g, w_g = moe.moe_route(cfg, gpu.x, gpu.x_scale, gpu.router_w, gpu.bias)
+    torch.cuda.synchronize()
+    other, swapped, _ = compare_routing(ids_g, w_g, ids, w, margin, wl.routed_scale, wl.E, keys)
+    print(f"route {wl.name}: other-set tokens={other} swapped-slot tokens={swapped} (margin<1e-6 only)")
+    s = w_g.sum(dim=1).cpu().numpy()
+    np.testing.assert_allclose(s, wl.routed_scale, rtol=1e-5)           # renormalised weights
+
+
+def test_permute(case):
+    wl, cpu, gpu, (p, ids, w, margin, offsets, sorted_pair, inv, _k) = case
+    cfg = moe.MoEConfig.from_workload(wl)
+    ids_d = torch.from_numpy(ids).cuda()
+    off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(off_g.cpu().numpy(), offsets)
+    assert np.array_equal(sp_g.cpu().numpy(), sorted_pair)
+    assert np.array_equal(inv_g.cpu().numpy(), inv)
+    n = check_tiles(tiles, ntiles, offsets, moe.moe_tile_rows(cfg))
+    assert n <= moe.moe_max_tiles(cfg)
+
+
+def _staged(case):
+    wl, cpu, gpu, (p, ids, w, margin, offsets, sorted_pair, inv, _k) = case
+    cfg = moe.MoEConfig.from_workload(wl)
+    ids_d = torch.from_numpy(ids).cuda()
+    off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_d)
+    tok = sorted_pair // wl.top_k
+    exp = ids.reshape(-1)[sorted_pair]
+    return wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv
+
+
+def test_gemm_swiglu(case):
+    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
+    act_g, _ = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
+    torch.cuda.synchronize()
+    ref = orc.swiglu_rows(p, tok, exp)
+    max_rel, mean_rel = err_stats(f64(act_g), ref)
+    print(f"swiglu {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e}")
+    assert max_rel <= 6e-3 and mean_rel <= 3e-3          # one bf16 rounding of an fp32 accumulation
+
+
+def test_gemm_down(case):
+    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
+    act_g, _ = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
+    y_g = moe.moe_grouped_gemm_down(cfg, act_g, None, gpu.w2, gpu.w2_scale, tiles, ntiles)
+    torch.cuda.synchronize()
+    ref = orc.down_rows(p, exp, f64(act_g))              # from the very activations the GPU consumed
+    max_rel, mean_rel = err_stats(f64(y_g), ref)
+    print(f"down {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e}")
+    assert max_rel <= 6e-3 and mean_rel <= 3e-3
+
+
+def test_combine(case):
+    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
+    g = torch.Generator().manual_seed(1)
+    y = torch.randn((cfg.P, wl.H), generator=g).bfloat16()
+    w32 = torch.from_numpy(w.astype(np.float32))
+    out_g = moe.moe_combine(cfg, y.cuda(), w32.cuda(), inv_g)
+    torch.cuda.synchronize()
+    ref = orc.combine(w32.numpy().astype(np.float64), inv, f64(y))
+    got = f64(out_g)
+    # fp32 sum of k exact products, one rounding to bf16: within half a bf16 ulp plus fp32 noise
+    assert (np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30).all()
+    ref_bits = torch.from_numpy(ref).to(torch.bfloat16)
+    assert (ref_bits.view(torch.int16) != out_g.cpu().view(torch.int16)).float().mean() < 1e-3
+
+
+def test_forward(case):
+    wl, cpu, gpu, (p, ids, w, margin, *_rest, keys) = case
+    out_g = moe.forward_inputs(gpu)
+    torch.cuda.synchronize()
+    out2 = moe.forward_inputs(gpu)
+    torch.cuda.synchronize()
+    assert torch.equal(out_g.view(torch.int16), out2.view(torch.int16)), "forward is not run-to-run identical"
+    ref, ids_r, w_r, margin_r = orc.forward(p)
+    cfg = moe.MoEConfig.from_workload(wl)
+    ids_g, w_g = moe.moe_route(cfg, gpu.x, gpu.x_scale, gpu.router_w, gpu.bias)
+    other, swapped, same_set = compare_routing(ids_g, w_g, ids_r, w_r, margin_r, wl.routed_scale, wl.E, keys)
+    got = f64(out_g)
+    assert np.isfinite(got).all()
+    max_rel, mean_rel = err_stats(got[same_set], ref[same_set])
+    print(f"forward {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e} tie-excused tokens={other}")
+    assert max_rel <= TOL_MAX[wl.fp8] and mean_rel <= TOL_MEAN[wl.fp8]
+
+
+def test_forward_zero_tokens_and_errors():
+    wl = syn.Workload("empty", T=0, H=128, I=64, E=8, top_k=2)
+    cfg = moe.MoEConfig.from_workload(wl)
+    ids = torch.empty((0, 2), dtype=torch.int32, device="cuda")
+    off, sp, inv, tiles, ntiles = moe.moe_permute(cfg, ids)
+    torch.cuda.synchronize()
+    assert off.cpu().tolist() == [0] * 9 and int(ntiles.item()) == 0
+    # workspace one byte short is refused before anything is enqueued
+    wl = syn.WORKLOADS["tiny"]
+    gpu = syn.make_inputs(wl, seed=0).to("cuda")
+    cfg = moe.MoEConfig.from_workload(wl)
+    small = torch.empty((moe.moe_workspace_size(cfg) - 256,), dtype=torch.uint8, device="cuda")
+    with pytest.raises(moe.MoEError, match="workspace"):
+        moe.moe_forward(cfg, gpu.x, None, gpu.router_w, None, gpu.w1, None, gpu.w2, None, workspace=small)
+
+
+def test_permute_drops_out_of_range_ids_and_handles_one_hot_expert():
+    wl = syn.Workload("drop", T=50, H=128, I=64, E=8, top_k=2)
+    cfg = moe.MoEConfig.from_workload(wl)
+    rng = np.random.default_rng(0)
+    ids = rng.integers(0, 8, size=(50, 2)).astype(np.int32)
+    ids[::7, 1] = -1
+    ids[3::11, 0] = 8
+    off, sp, inv, tiles, ntiles = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
+    torch.cuda.synchronize()
+    flat = ids.reshape(-1)
+    keep = (flat >= 0) & (flat < 8)
+    off_r, sp_r, inv_r = orc.permute(flat[keep].reshape(-1, 1), 8)      # oracle on the kept pairs
+    kept_pairs = np.nonzero(keep)[0]
+    assert np.array_equal(off.cpu().numpy(), off_r)
+    assert np.array_equal(sp.cpu().numpy()[: keep.sum()], kept_pairs[sp_r])
+    inv_g = inv.cpu().numpy()
+    assert (inv_g[~keep] == -1).all() and np.array_equal(inv_g[keep], inv_r)
+    # every pair on one expert: maximum rows for a single segment
+    ids = np.full((50, 2), 5, dtype=np.int32)
+    off, sp, inv, tiles, ntiles = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
+    torch.cuda.synchronize()
+    off_r, sp_r, inv_r = orc.permute(ids, 8)
+    assert np.array_equal(off.cpu().numpy(), off_r) and np.array_equal(sp.cpu().numpy(), sp_r)
+    check_tiles(tiles, ntiles, off_r, moe.moe_tile_rows(cfg))

@@ -1,0 +1,108 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol include/moe.h declares, and refuses bad problem statements before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_19128_amd import binding as moe
+from paper_2602_19128_amd import synthetic as syn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(moe.LIB_PATH):
+        from paper_2602_19128_amd import build
+        build.build(verbose=False)
+    return moe.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert set(names) == set(moe.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_config_struct_matches_header():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    body = re.search(r"typedef struct moe_config \{(.*?)\} moe_config;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if decl:
+            fields += [f.strip() for f in decl.split(None, 1)[1].split(",")]
+    assert fields == [f[0] for f in moe.MoEConfig._fields_]
+    assert C.sizeof(moe.MoEConfig) == 4 * len(fields)
+    assert moe.TILE_INTS * 4 == 32
+
+
+def test_size_queries_and_tile_heights(lib):
+    for name, wl in syn.WORKLOADS.items():
+        if wl.fp8:
+            continue
+        cfg = moe.MoEConfig.from_workload(wl)
+        rows = moe.moe_tile_rows(cfg)
+        assert rows in (32, 64, 128)
+        P = wl.T * wl.top_k
+        assert moe.moe_max_tiles(cfg) >= -(-P // rows)
+        ws = moe.moe_workspace_size(cfg)
+        assert ws % 256 == 0 and ws >= P * wl.I * 2 + P * wl.H * 2
+        assert moe.moe_route_workspace_size(cfg) >= wl.T * wl.E * 4
+
+
+@pytest.mark.parametrize("change, code", [
+    (dict(top_k=9), -1),                 # top_k > E
+    (dict(H=100), -2),                   # H not a multiple of 64
+    (dict(E=1024, top_k=2), -2),         # too many experts
+    (dict(scoring=7), -1),
+    (dict(n_group=3), -1),               # E % n_group != 0
+    (dict(n_group=4, topk_group=5), -1),
+    (dict(n_group=4, topk_group=1, group_score_topn=2, top_k=3), -1),   # top_k > eligible experts
+    (dict(n_group=4, topk_group=2, group_score_topn=3), -1),            # topn > group size
+])
+def test_bad_problem_statements_are_refused(lib, change, code):
+    cfg = moe.MoEConfig(T=16, H=256, I=128, E=8, top_k=2, scoring=0, renormalize=1, n_group=1,
+                        topk_group=1, group_score_topn=2, dtype=0, routed_scale=1.0)
+    for k, v in change.items():
+        setattr(cfg, k, v)
+    assert moe.moe_workspace_size(cfg) == 0
+    one = C.c_void_p(256)                # never dereferenced: validation fails first
+    rc = lib.moe_forward(C.byref(cfg), one, None, one, None, one, None, one, None, one, one, C.c_size_t(1 << 40), None)
+    assert rc == code
+    rc = lib.moe_route(C.byref(cfg), one, None, one, None, one, one, one, C.c_size_t(1 << 40), None)
+    assert rc == code
+
+
+def test_null_pointers_and_small_workspace_are_refused(lib):
+    cfg = moe.MoEConfig.from_workload(syn.WORKLOADS["tiny"])
+    one = C.c_void_p(256)
+    rc = lib.moe_forward(C.byref(cfg), None, None, one, None, one, None, one, None, one, one, C.c_size_t(1 << 40), None)
+    assert rc == -1
+    rc = lib.moe_forward(C.byref(cfg), one, None, one, None, one, None, one, None, one, one, C.c_size_t(16), None)
+    assert rc == -3
+    rc = lib.moe_forward(C.byref(cfg), one, None, one, None, one, None, one, None, one, C.c_void_p(264),
+                         C.c_size_t(1 << 40), None)
+    assert rc == -1                      # workspace not 256-byte aligned
+    assert lib.moe_error_string(-3) == b"workspace too small"
+    assert lib.moe_forward(None, one, None, one, None, one, None, one, None, one, one, C.c_size_t(0), None) == -1
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    wl = syn.WORKLOADS["tiny"]
+    inp = syn.make_inputs(wl, seed=0)
+    cfg = moe.MoEConfig.from_workload(wl)
+    with pytest.raises(moe.MoEError):
+        moe.moe_combine(cfg, torch.zeros(cfg.P, wl.H, dtype=torch.bfloat16), torch.zeros(wl.T, wl.top_k),
+                        torch.zeros(cfg.P, dtype=torch.int32))
