@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused MoE forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one whole layer forward (route, sort-scatter, gate/up GEMM + SiLU gating,
+down GEMM, combine) through the C ABI on synthetic tensors that are resident in
+HBM before the timed region starts.  Prints one JSON line: latency per forward,
+TFLOP/s and GB/s with their fractions of the MI355X peaks, the roofline of the
+dominant kernel (gate/up grouped GEMM) from HIP events recorded around it in the
+timed region, and the CPU oracle timed on a bounded token sample of the same
+workload.
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0                                   # MI355X HBM3E
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}       # dense
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime PyTorch already loaded (plumbing only)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def make(self, n):
+        arr = (C.c_void_p * n)()
+        for i in range(n):
+            ev = C.c_void_p()
+            rc = self.hip.hipEventCreate(C.byref(ev))
+            assert rc == 0, f"hipEventCreate failed: {rc}"
+            arr[i] = ev
+        return arr
+
+    def ms(self, a, b):
+        out = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(out), a, b)
+        assert rc == 0, f"hipEventElapsedTime failed: {rc}"
+        return float(out.value)
+
+    def free(self, arr):
+        for ev in arr:
+            self.hip.hipEventDestroy(ev)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="mixtral_prefill")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
+                    help="CPU work budget for the oracle sample; 0 skips the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU kernel path only: run with --gpus 1 "
+              "(this library has no multi-GPU code; see DESIGN.md on how the layer would shard)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_19128_amd import binding as moe
+    from paper_2602_19128_amd import synthetic as syn
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    moe.load()
+    wl = syn.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    inp = syn.make_inputs(wl, seed=args.seed, device=dev)
+    cfg = moe.MoEConfig.from_workload(wl)
+    out = torch.empty((wl.T, wl.H), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty((moe.moe_workspace_size(cfg),), dtype=torch.uint8, device=dev)
+    call = lambda ev=None: moe.moe_forward(cfg, inp.x, inp.x_scale, inp.router_w, inp.bias, inp.w1, inp.w1_scale,
+                                           inp.w2, inp.w2_scale, out=out, workspace=ws, events=ev)
+
+    hip = HipEvents()
+    K, W = args.steps, args.warmup
+    events = [hip.make(moe.FORWARD_EVENTS) for _ in range(K)]
+    for _ in range(W):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        call(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+
+    step_ms = {name: 0.0 for name in moe.STEP_NAMES}
+    for ev in events:
+        for j, name in enumerate(moe.STEP_NAMES):
+            step_ms[name] += hip.ms(ev[j], ev[j + 1]) / K
+    gpu_ms = sum(hip.ms(ev[0], ev[moe.FORWARD_EVENTS - 1]) for ev in events) / K
+    for ev in events:
+        hip.free(ev)
+
+    # ---- work the method itself has to do (no padding flops, no skipped experts) -------------
+    ids, w = moe.moe_route(cfg, inp.x, inp.x_scale, inp.router_w, inp.bias)
+    counts = torch.bincount(ids.reshape(-1).long(), minlength=wl.E).cpu().numpy()
+    e_active = int((counts > 0).sum())
+    T, H, I, E, k = wl.T, wl.H, wl.I, wl.E, wl.top_k
+    P = T * k
+    bw = 1 if wl.fp8 else 2                      # bytes per weight / activation payload element
+    scale_w = (E * (2 * I // 128) * (H // 128) + E * (H // 128) * (I // 128)) * 4 if wl.fp8 else 0
+    flops = 6.0 * H * I * P + 2.0 * T * E * H
+    bytes_min = e_active * 3 * H * I * bw + scale_w + T * H * bw + E * H * 4 + T * H * 2
+    sec = ms_per_step * 1e-3
+    kind = "fp8" if wl.fp8 else "bf16"
+    tflops = flops / sec / 1e12
+    gbps = bytes_min / sec / 1e9
+
+    # dominant kernel: gate/up grouped GEMM.  Algorithmic bytes of one launch: the active experts'
+    # gate/up weights once, the hidden states once, the activations written once.
+    g1_bytes = e_active * 2 * I * H * bw + T * H * bw + P * I * bw
+    if wl.fp8:
+        g1_bytes += e_active * (2 * I // 128) * (H // 128) * 4 + T * (H // 128) * 4 + P * (I // 128) * 4
+    g1_sec = step_ms["gemm_swiglu"] * 1e-3
+    g1_gbps = g1_bytes / g1_sec / 1e9
+    roofline = {"kernel": "grouped_gemm_swiglu", "bound": "hbm", "achieved": round(g1_gbps, 1),
+                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g1_gbps / PEAK_HBM_GBPS, 4),
+                "traffic": None, "bytes_per_launch": int(g1_bytes), "avg_launch_us": round(g1_sec * 1e6, 2),
+                "tflops": round(4.0 * H * I * P / g1_sec / 1e12, 1),
+                "frac_mfma": round(4.0 * H * I * P / g1_sec / 1e12 / PEAK_MFMA_TFLOPS[kind], 4)}
+
+    # ---- CPU oracle on a bounded token sample of the same workload ------------------------------
+    cpu_baseline = None
+    parity = None
+    if args.cpu_baseline_seconds > 0:
+        from oracle import moe_oracle as orc
+        cpu = inp.to("cpu")
+        prob = orc.problem_from_inputs(cpu)
+        rng = np.random.default_rng(args.seed)
+        order = rng.permutation(T).astype(np.int32)
+        c0 = time.perf_counter()
+        ref0, *_ = orc.forward_tokens(prob, order[:1])
+        per_tok = time.perf_counter() - c0
+        n = int(max(1, min(T - 1, args.cpu_baseline_seconds / max(per_tok, 1e-9))))
+        sample = order[1:1 + n]
+        c0 = time.perf_counter()
+        ref, ids_r, w_r, margin_r = orc.forward_tokens(prob, sample)
+        cpu_s = time.perf_counter() - c0
+        cpu_baseline = {"value": round(cpu_s / n * T * 1e6, 1), "unit": "us", "cores": orc.num_threads(),
+                        "kind": "oracle",
+                        "sample": f"{n} of {T} tokens (all {k} experts each) in {cpu_s:.1f} s, scaled by T/n"}
+        got = out[torch.from_numpy(sample.astype(np.int64)).to(dev)].float().cpu().numpy().astype(np.float64)
+        same = np.array([sorted(a) == sorted(b) for a, b in
+                         zip(ids[torch.from_numpy(sample.astype(np.int64)).to(dev)].cpu().numpy(), ids_r)])
+        err = np.abs(got[same] - ref[same])
+        parity = {"tokens": int(same.sum()), "tie_excused": int((~same).sum()),
+                  "max_rel": float(err.max() / np.abs(ref[same]).max()),
+                  "mean_rel": float(err.sum() / np.abs(ref[same]).sum())}
+
+    line = {
+        "metric": "fused_moe_forward_latency", "value": round(ms_per_step * 1e3, 2), "unit": "us",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": kind,
+        "data": "synthetic", "config": {"workload": wl.name, "T": T, "H": H, "I": I, "E": E, "top_k": k,
+                                        "scoring": wl.scoring, "n_group": wl.n_group, "seed": args.seed,
+                                        "tile_rows": moe.moe_tile_rows(cfg), "active_experts": e_active,
+                                        "max_over_mean_load": round(float(counts.max() / max(counts.mean(), 1e-9)), 2)},
+        "tflops": round(tflops, 1), "frac_mfma_peak": round(tflops / PEAK_MFMA_TFLOPS[kind], 4),
+        "gbps": round(gbps, 1), "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
+        "roofline_time_us": round(max(flops / (PEAK_MFMA_TFLOPS[kind] * 1e12), bytes_min / (PEAK_HBM_GBPS * 1e9)) * 1e6, 1),
+        "gpu_event_us": round(gpu_ms * 1e3, 2),
+        "step_us": {n_: round(v * 1e3, 2) for n_, v in step_ms.items()},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_sample": parity,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

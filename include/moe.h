@@ -153,6 +153,19 @@ int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, cons
                 const float *w2_scale, void *out, void *workspace, size_t workspace_bytes,
                 void *stream);
 
+/*
+ * moe_forward with step boundaries marked for timing: `events` is a HOST array of
+ * MOE_FORWARD_EVENTS hipEvent_t handles (created by the caller) that are recorded
+ * on `stream` before routing and after each of the five steps, in pipeline order
+ * (route, sort-scatter, gate/up GEMM, down GEMM, combine).  The kernels and their
+ * launch configuration are exactly those of moe_forward.
+ */
+enum { MOE_FORWARD_EVENTS = 6 };
+int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+                       const float *bias, const void *w1, const float *w1_scale, const void *w2,
+                       const float *w2_scale, void *out, void *workspace, size_t workspace_bytes,
+                       void *stream, void *const *events);
+
 /* Text for an error code; the hipError_t of the last failed launch on this thread. */
 const char *moe_error_string(int code);
 int moe_last_hip_error(void);

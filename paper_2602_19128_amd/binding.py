@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libmoe_gfx950.so")
 EXPORTS = [
     "moe_tile_rows", "moe_max_tiles", "moe_route_workspace_size", "moe_workspace_size",
     "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm_down",
-    "moe_combine", "moe_forward", "moe_error_string", "moe_last_hip_error",
+    "moe_combine", "moe_forward", "moe_forward_marked", "moe_error_string", "moe_last_hip_error",
 ]
 
 TILE_INTS = 8            # int32 fields of one moe_tile record
@@ -80,6 +80,8 @@ def load():
     lib.moe_combine.argtypes = [cfgp, vp, f32p, i32p, vp, vp]
     lib.moe_forward.restype = C.c_int
     lib.moe_forward.argtypes = [cfgp, vp, f32p, f32p, f32p, vp, f32p, vp, f32p, vp, vp, C.c_size_t, vp]
+    lib.moe_forward_marked.restype = C.c_int
+    lib.moe_forward_marked.argtypes = lib.moe_forward.argtypes + [C.POINTER(C.c_void_p)]
     lib.moe_error_string.restype = C.c_char_p
     lib.moe_error_string.argtypes = [C.c_int]
     lib.moe_last_hip_error.restype = C.c_int
@@ -205,7 +207,13 @@ def moe_combine(cfg, y, w, inv):
     return out
 
 
-def moe_forward(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out=None, workspace=None):
+FORWARD_EVENTS = 6
+STEP_NAMES = ("route", "permute", "gemm_swiglu", "gemm_down", "combine")
+
+
+def moe_forward(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out=None, workspace=None,
+                events=None):
+    """`events`: optional ctypes array of FORWARD_EVENTS hipEvent_t handles (see moe_forward_marked)."""
     dev = x.device
     _expect(x, (cfg.T, cfg.H), _payload(cfg), "x")
     _expect(router_w, (cfg.E, cfg.H), torch.float32, "router_w")
@@ -213,8 +221,12 @@ def moe_forward(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out
     _expect(w2, (cfg.E, cfg.H, cfg.I), _payload(cfg), "w2")
     out = torch.empty((cfg.T, cfg.H), dtype=torch.bfloat16, device=dev) if out is None else out
     workspace = _bytes(moe_workspace_size(cfg), dev) if workspace is None else workspace
-    rc = load().moe_forward(C.byref(cfg), _p(x), _p(x_scale), _p(router_w), _p(bias), _p(w1), _p(w1_scale),
-                            _p(w2), _p(w2_scale), _p(out), _p(workspace), C.c_size_t(workspace.numel()), _stream())
+    args = (C.byref(cfg), _p(x), _p(x_scale), _p(router_w), _p(bias), _p(w1), _p(w1_scale), _p(w2),
+            _p(w2_scale), _p(out), _p(workspace), C.c_size_t(workspace.numel()), _stream())
+    if events is None:
+        rc = load().moe_forward(*args)
+    else:
+        rc = load().moe_forward_marked(*args, events)
     _check(rc, "moe_forward")
     return out
 

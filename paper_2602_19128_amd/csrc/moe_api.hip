@@ -153,9 +153,10 @@ int moe_combine(const moe_config *cfg, const void *y, const float *w, const int3
     return launch_combine(*cfg, y, w, inv, out, (hipStream_t)stream);
 }
 
-int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
-                const float *bias, const void *w1, const float *w1_scale, const void *w2,
-                const float *w2_scale, void *out, void *workspace, size_t workspace_bytes, void *stream)
+int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+                       const float *bias, const void *w1, const float *w1_scale, const void *w2,
+                       const float *w2_scale, void *out, void *workspace, size_t workspace_bytes,
+                       void *stream, void *const *events)
 {
     int rc = validate(cfg);
     if (rc != MOE_OK) return rc;
@@ -179,16 +180,34 @@ int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, cons
     void *y = ws + l.y;
     hipStream_t s = (hipStream_t)stream;
     const int tr = tile_rows_for(*cfg), mt = max_tiles_for(*cfg);
+    int mark_at = 0;
+    auto mark = [&]() -> int {
+        if (events == nullptr) return MOE_OK;
+        hipError_t e = hipEventRecord((hipEvent_t)events[mark_at++], s);
+        if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
+        return MOE_OK;
+    };
 
+    if ((rc = mark()) != MOE_OK) return rc;
     rc = launch_route(*cfg, x, x_scale, router_w, bias, ids, w, ws + l.route, s);
-    if (rc != MOE_OK) return rc;
+    if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
     rc = launch_permute(*cfg, tr, mt, ids, offsets, sorted_pair, inv, tiles, ntiles, s);
-    if (rc != MOE_OK) return rc;
+    if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
     rc = launch_gemm_swiglu(*cfg, tr, mt, x, x_scale, w1, w1_scale, sorted_pair, tiles, ntiles, act, act_scale, s);
-    if (rc != MOE_OK) return rc;
+    if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
     rc = launch_gemm_down(*cfg, tr, mt, act, act_scale, w2, w2_scale, tiles, ntiles, y, s);
+    if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
+    rc = launch_combine(*cfg, y, w, inv, out, s);
     if (rc != MOE_OK) return rc;
-    return launch_combine(*cfg, y, w, inv, out, s);
+    return mark();
+}
+
+int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+                const float *bias, const void *w1, const float *w1_scale, const void *w2,
+                const float *w2_scale, void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return moe_forward_marked(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out, workspace,
+                              workspace_bytes, stream, nullptr);
 }
 
 const char *moe_error_string(int code)

@@ -135,8 +135,12 @@ class MoEInputs:
                          mv(self.w2), mv(self.x_scale), mv(self.w1_scale), mv(self.w2_scale))
 
 
-def make_inputs(wl: Workload, seed: int = 0, device="cpu") -> MoEInputs:
+def make_inputs(wl: Workload, seed: int = 0, device="cpu",
+                weights_from: Optional[MoEInputs] = None) -> MoEInputs:
     """Draw one workload's tensors.
+
+    `weights_from`: reuse the router and expert weights of an earlier draw with the
+    same H/I/E/dtype and seed (they do not depend on T), drawing only x and bias.
 
     hidden ~ N(0,1); router W ~ N(0,1/H) fp32; expert weights ~ N(0,1/fan_in);
     bias ~ U(-0.1,0.1) (+hot_bias on the hot experts).  bf16 workloads round to
@@ -154,10 +158,18 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu") -> MoEInputs:
         hot = hot_expert_ids(wl)
         if hot:
             bias[torch.tensor(hot, device=dev)] += wl.hot_bias
+    if wl.fp8:
+        x, x_scale = quantize_rows_1x128(x32)
+    else:
+        x, x_scale = x32.to(torch.bfloat16), None
+    if weights_from is not None:
+        o = weights_from
+        assert (o.wl.H, o.wl.I, o.wl.E, o.wl.fp8) == (H, I, E, wl.fp8) and o.w1.device.type == dev.type
+        return MoEInputs(wl, x, o.router_w, bias, o.w1, o.w2, x_scale, o.w1_scale, o.w2_scale)
     wdt = torch.float8_e4m3fn if wl.fp8 else torch.bfloat16
     w1 = torch.empty((E, 2 * I, H), dtype=wdt, device=dev)
     w2 = torch.empty((E, H, I), dtype=wdt, device=dev)
-    w1_scale = w2_scale = x_scale = None
+    w1_scale = w2_scale = None
     if wl.fp8:
         w1_scale = torch.empty((E, 2 * I // QBLOCK, H // QBLOCK), dtype=torch.float32, device=dev)
         w2_scale = torch.empty((E, H // QBLOCK, I // QBLOCK), dtype=torch.float32, device=dev)
@@ -173,8 +185,4 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu") -> MoEInputs:
             w1[e] = a.to(torch.bfloat16)
             w2[e] = b.to(torch.bfloat16)
         del a, b
-    if wl.fp8:
-        x, x_scale = quantize_rows_1x128(x32)
-    else:
-        x = x32.to(torch.bfloat16)
     return MoEInputs(wl, x, router_w, bias, w1, w2, x_scale, w1_scale, w2_scale)

@@ -1,0 +1,88 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times
+(one moe_forward call on a preallocated workspace).
+
+The oracle cannot run these sizes in full, so: routing and the sort-scatter are
+compared for every token (they need no expert weights), and the layer output is
+compared on a seeded sample of tokens the oracle computes one by one.  Tensors
+are drawn on the GPU and copied to the host for the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as orc
+from paper_2602_19128_amd import binding as moe
+from paper_2602_19128_amd import synthetic as syn
+from parity_util import TOL_MAX, TOL_MEAN, check_tiles, choice_keys, compare_routing, err_stats, f64
+
+pytestmark = pytest.mark.gpu
+
+SAMPLE_TOKENS = 24
+
+
+def _check_workload(gpu, host_w, sample_tokens=SAMPLE_TOKENS):
+    wl = gpu.wl
+    print(f"\n[full-size] {wl}", flush=True)
+    cfg = moe.MoEConfig.from_workload(wl)
+    out = torch.empty((wl.T, wl.H), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty((moe.moe_workspace_size(cfg),), dtype=torch.uint8, device="cuda")
+    moe.moe_forward(cfg, gpu.x, gpu.x_scale, gpu.router_w, gpu.bias, gpu.w1, gpu.w1_scale, gpu.w2, gpu.w2_scale,
+                    out=out, workspace=ws)
+    torch.cuda.synchronize()
+    first = out.clone()
+    moe.moe_forward(cfg, gpu.x, gpu.x_scale, gpu.router_w, gpu.bias, gpu.w1, gpu.w1_scale, gpu.w2, gpu.w2_scale,
+                    out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first.view(torch.int16), out.view(torch.int16)), "not run-to-run identical"
+    assert torch.isfinite(out.float()).all()
+
+    # routing + sort-scatter for every token
+    host = syn.MoEInputs(wl, gpu.x.cpu(), host_w.router_w, None if gpu.bias is None else gpu.bias.cpu(),
+                         host_w.w1, host_w.w2, None if gpu.x_scale is None else gpu.x_scale.cpu(),
+                         host_w.w1_scale, host_w.w2_scale)
+    p = orc.problem_from_inputs(host)
+    z = orc.router_logits(p)
+    ids_r, w_r, margin = orc.route(p, z)
+    ids_g, w_g = moe.moe_route(cfg, gpu.x, gpu.x_scale, gpu.router_w, gpu.bias)
+    other, swapped, same_set = compare_routing(ids_g, w_g, ids_r, w_r, margin, wl.routed_scale, wl.E,
+                                               choice_keys(p, z))
+    off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_g)
+    torch.cuda.synchronize()
+    off_r, sp_r, inv_r = orc.permute(ids_g.cpu().numpy(), wl.E)      # oracle on the GPU's own routing
+    assert np.array_equal(off_g.cpu().numpy(), off_r)
+    assert np.array_equal(sp_g.cpu().numpy(), sp_r) and np.array_equal(inv_g.cpu().numpy(), inv_r)
+    check_tiles(tiles, ntiles, off_r, moe.moe_tile_rows(cfg))
+    load = np.diff(off_r)
+    print(f"  routing: tie-excused tokens={other} swapped slots={swapped} of {wl.T}; "
+          f"active experts={(load > 0).sum()} max/mean load={load.max() / load.mean():.2f}", flush=True)
+
+    # layer output on sampled tokens
+    rng = np.random.default_rng(0)
+    sample = np.sort(rng.choice(wl.T, size=min(sample_tokens, wl.T), replace=False)).astype(np.int32)
+    ref, ids_s, w_s, margin_s = orc.forward_tokens(p, sample)
+    keep = same_set[sample]
+    got = f64(out[torch.from_numpy(sample.astype(np.int64)).cuda()])
+    max_rel, mean_rel = err_stats(got[keep], ref[keep])
+    print(f"  output on {keep.sum()} sampled tokens: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e}", flush=True)
+    assert keep.sum() >= len(sample) // 2
+    assert max_rel <= TOL_MAX[wl.fp8] and mean_rel <= TOL_MEAN[wl.fp8]
+
+
+def test_mixtral_prefill_full_size():
+    gpu = syn.make_inputs(syn.WORKLOADS["mixtral_prefill"], seed=0, device="cuda")
+    _check_workload(gpu, gpu.to("cpu"))
+
+
+@pytest.fixture(scope="module")
+def dsv3():
+    gpu = syn.make_inputs(syn.WORKLOADS["dsv3_prefill"], seed=0, device="cuda")
+    print("\n[full-size] copying DeepSeek-V3-shaped weights to the host for the oracle", flush=True)
+    return gpu, gpu.to("cpu")
+
+
+@pytest.mark.parametrize("name", ["dsv3_decode", "dsv3_prefill", "dsv3_prefill_skew"])
+def test_dsv3_full_size(dsv3, name):
+    base, host_w = dsv3
+    gpu = base if name == "dsv3_prefill" else syn.make_inputs(syn.WORKLOADS[name], seed=0, device="cuda",
+                                                               weights_from=base)
+    _check_workload(gpu, host_w)
