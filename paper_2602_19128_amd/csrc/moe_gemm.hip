@@ -4,9 +4,15 @@
 // Both GEMMs are C[m,n] = sum_k A[m,k] * W[e,n,k] with A rows and W rows contiguous
 // along k, so both operands are fetched as 16-byte pieces of a row.  A workgroup of
 // four wavefronts owns one row tile of one expert times BN weight rows.  Each K
-// step of 64 is staged through LDS (XOR-swizzled 128-byte rows, conflict-free for the
-// 16-byte MFMA fragment reads); the next stage's global loads are issued before the
-// MFMAs of the current one and written to the other LDS buffer afterwards.
+// step of 64 elements is one 128-byte LDS row per tile row.  Global memory is copied
+// straight into LDS (global_load_lds, 16 bytes per lane, no register staging): the
+// copy of step kt+1 is issued before the MFMAs of step kt and only waited for at the
+// barrier that ends the step, so HBM latency hides behind the matrix cores.
+//
+// LDS layout: the hardware places lane l of a direct load at base + 16*l, so a
+// wavefront fills 8 consecutive 128-byte rows.  To keep the 16-byte MFMA fragment
+// reads conflict-free, physical chunk pc of row r holds logical chunk pc ^ (r & 7);
+// the permutation is applied on the global-address side of the copy.
 //
 //   gate/up GEMM: A rows are gathered from x through the sorted pair list; a wavefront
 //                 holds matching gate and up columns in the same lanes, so
@@ -28,7 +34,10 @@ constexpr int GM_BK = 64;                 // k elements per LDS stage (one 128-b
 constexpr int GM_THREADS = 256;
 constexpr int GM_XCDS = 8;
 
-__device__ inline int lds_off(int row, int chunk)      // byte offset of a 16-byte chunk, swizzled
+#define MOE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define MOE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+__device__ inline int lds_off(int row, int chunk)      // byte offset of logical 16-byte chunk `chunk` of `row`
 {
     return row * 128 + ((chunk ^ (row & 7)) << 4);
 }
@@ -44,7 +53,7 @@ __global__ __launch_bounds__(GM_THREADS) void grouped_gemm_bf16_kernel(
     constexpr int MI = WTM / 32, NI = WTN / 32;                // 32x32 MFMA blocks per wavefront
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wavefront tile is made of 32x32 blocks");
     static_assert(!SWIGLU || NI % 2 == 0, "gate and up halves live in one wavefront");
-    constexpr int A_PASS = BM / 32, B_PASS = BN / 32;          // 32 rows x 8 chunks per loader pass
+    constexpr int A_PASS = BM / 32, B_PASS = BN / 32;          // one pass = 32 rows = 4 wavefronts x 8 rows
     constexpr int STAGE_BYTES = (BM + BN) * 128;
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -64,7 +73,8 @@ __global__ __launch_bounds__(GM_THREADS) void grouped_gemm_bf16_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int lrow = tid >> 3, lchunk = tid & 7;               // loader coordinates
+    const int lrow = tid >> 3;                                 // loader: row inside a 32-row pass
+    const int lchunk = (tid & 7) ^ (lrow & 7);                 // logical chunk that lands on this lane's LDS slot
 
     // ---- global row pointers of the loader ---------------------------------
     const int w_rows = SWIGLU ? 2 * n_out : n_out;
@@ -105,52 +115,49 @@ __global__ __launch_bounds__(GM_THREADS) void grouped_gemm_bf16_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 a_reg[A_PASS], b_reg[B_PASS];
-    auto fetch = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_PASS; ++i) a_reg[i] = *reinterpret_cast<const uint4 *>(a_ptr[i] + k0);
-#pragma unroll
-        for (int i = 0; i < B_PASS; ++i) b_reg[i] = *reinterpret_cast<const uint4 *>(b_ptr[i] + k0);
-    };
-    auto stash = [&](int buf) {
-        unsigned char *sa = smem + buf * STAGE_BYTES;
-        unsigned char *sb = sa + BM * 128;
-#pragma unroll
-        for (int i = 0; i < A_PASS; ++i)
-            *reinterpret_cast<uint4 *>(sa + lds_off(lrow + 32 * i, lchunk)) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_PASS; ++i)
-            *reinterpret_cast<uint4 *>(sb + lds_off(lrow + 32 * i, lchunk)) = b_reg[i];
-    };
-
     const int nk = K / GM_BK;
-    fetch(0);
-    stash(0);
+    // LDS destination of this wavefront inside a 32-row pass (the hardware adds 16 * lane)
+    unsigned char *const wave_dst = smem + wave * 1024;
+
+#define MOE_COPY_STAGE(k0, buf)                                                                         \
+    {                                                                                                   \
+        unsigned char *da_ = wave_dst + (buf) * STAGE_BYTES;                                            \
+        unsigned char *db_ = da_ + BM * 128;                                                            \
+        _Pragma("unroll") for (int i = 0; i < A_PASS; ++i)                                              \
+            __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(a_ptr[i] + (k0)), MOE_LDS_PTR(da_ + i * 4096), 16, 0, 0); \
+        _Pragma("unroll") for (int i = 0; i < B_PASS; ++i)                                              \
+            __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(b_ptr[i] + (k0)), MOE_LDS_PTR(db_ + i * 4096), 16, 0, 0); \
+    }
+#define MOE_COMPUTE_STAGE(buf)                                                                          \
+    {                                                                                                   \
+        const unsigned char *sa_ = smem + (buf) * STAGE_BYTES + (wm * WTM) * 128;                       \
+        const unsigned char *sb_ = smem + (buf) * STAGE_BYTES + BM * 128 + (wn * WTN) * 128;            \
+        _Pragma("unroll") for (int kk = 0; kk < GM_BK / 16; ++kk) {                                     \
+            const int chunk = kk * 2 + (lane >> 5);                                                     \
+            bf16x8 af[MI], bfr[NI];                                                                     \
+            _Pragma("unroll") for (int i = 0; i < MI; ++i)                                              \
+                af[i] = *reinterpret_cast<const bf16x8 *>(sa_ + lds_off(i * 32 + (lane & 31), chunk));  \
+            _Pragma("unroll") for (int j = 0; j < NI; ++j)                                              \
+                bfr[j] = *reinterpret_cast<const bf16x8 *>(sb_ + lds_off(j * 32 + (lane & 31), chunk)); \
+            _Pragma("unroll") for (int i = 0; i < MI; ++i)                                              \
+                _Pragma("unroll") for (int j = 0; j < NI; ++j)                                          \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
+        }                                                                                               \
+    }
+
+    // K loop.  __syncthreads() waits for this wavefront's outstanding copies (it carries a
+    // workgroup-scope fence) and then for the other wavefronts, so after it every copy into
+    // the next buffer has landed and every read of the current buffer is done.
+    MOE_COPY_STAGE(0, 0)
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) fetch((kt + 1) * GM_BK);
-        const unsigned char *sa = smem + buf * STAGE_BYTES + (wm * WTM) * 128;
-        const unsigned char *sb = smem + buf * STAGE_BYTES + BM * 128 + (wn * WTN) * 128;
-#pragma unroll
-        for (int kk = 0; kk < GM_BK / 16; ++kk) {
-            const int chunk = kk * 2 + (lane >> 5);
-            bf16x8 af[MI], bfr[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(sa + lds_off(i * 32 + (lane & 31), chunk));
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(sb + lds_off(j * 32 + (lane & 31), chunk));
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) stash(buf ^ 1);
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        MOE_COPY_STAGE((kt + 1) * GM_BK, (kt + 1) & 1)
+        MOE_COMPUTE_STAGE(kt & 1)
         __syncthreads();
     }
+    MOE_COMPUTE_STAGE((nk - 1) & 1)
+#undef MOE_COPY_STAGE
+#undef MOE_COMPUTE_STAGE
 
     // ---- epilogue: accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
     const int lcol = lane & 31, lrow4 = (lane >> 5) * 4;
