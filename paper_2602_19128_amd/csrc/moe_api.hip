@@ -1,6 +1,8 @@
 // C ABI of the MoE library: argument checks, workspace carving, step sequencing.
 #include "moe_internal.hpp"
 
+#include <math.h>
+
 namespace moe {
 
 static thread_local int g_last_hip_error = 0;
@@ -34,11 +36,16 @@ int validate(const moe_config *c)
     return MOE_OK;
 }
 
+// Tile height: the smallest of 16..256 that holds an expert's rows with a binomial safety
+// margin (mean + 4 sigma of a balanced router), so that almost every expert is one tile and its
+// weights are streamed exactly once.
 int tile_rows_for(const moe_config &c)
 {
-    const long long pairs = (long long)c.T * c.top_k;
-    const long long avg = pairs / c.E;
-    return avg >= 96 ? 128 : avg >= 40 ? 64 : 32;
+    const double mean = (double)c.T * c.top_k / c.E;
+    const double want = mean + 4.0 * sqrt(mean);
+    int rows = 16;
+    while (rows < 256 && rows < want) rows *= 2;
+    return rows;
 }
 
 int max_tiles_for(const moe_config &c)
