@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mixtral_prefill")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="override the workload's token count (supplementary points; not the headline config)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
                     help="CPU work budget for the oracle sample; 0 skips the CPU baseline")
@@ -78,6 +80,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     moe.load()
     wl = syn.WORKLOADS[args.workload]
+    if args.tokens > 0:
+        wl = wl.replace(T=args.tokens, name=f"{wl.name}_T{args.tokens}")
     dev = torch.device("cuda:0")
     inp = syn.make_inputs(wl, seed=args.seed, device=dev)
     cfg = moe.MoEConfig.from_workload(wl)

@@ -6,24 +6,25 @@
 // few hundred) against large weight matrices, so the weights must stream from HBM exactly
 // once and at full rate.  The kernel is built around that:
 //
-//  * A workgroup of 8 wavefronts owns ALL rows of one expert tile (up to 16*MB_MAX) times a
+//  * A workgroup of NW wavefronts owns ALL rows of one expert tile (up to 16*MB_MAX) times a
 //    slab of weight rows; wavefront w owns two blocks of 16 weight rows (gate + matching up
-//    rows, or 32 consecutive down-projection rows).  Nothing is shared between wavefronts on
-//    the weight side, so weights go HBM -> VGPR directly in the MFMA operand layout (lane l
-//    holds 16 bytes of weight row l%16), prefetched D K-steps ahead through D+1 rotating
-//    register sets.  No LDS round trip and no barrier stands between HBM and the matrix core.
-//  * The token rows (x gathered through the sorted pair list, or act) are shared by all
-//    wavefronts: they are copied global -> LDS directly (global_load_lds), D stages ahead in a
-//    ring of D+1 stages, and read as the second MFMA operand.  Physical 16-byte chunk pc of
-//    LDS row r holds logical chunk pc ^ (r & 7) (applied on the global-address side of the
-//    copy) which keeps the fragment reads spread over the banks.
+//    rows, or 32 consecutive down-projection rows).
+//  * Every global read is a direct global -> LDS copy (global_load_lds, 16 bytes per lane) whose
+//    64 lanes cover 8 rows x 128 contiguous bytes: whole cache lines per instruction.  (Loading
+//    weights straight into the MFMA register layout would touch 16 rows x 64 bytes per
+//    instruction, half lines, which measures ~20% slower on this memory system.)  Weights land
+//    in a ring private to the owning wavefront (no barrier on the weight path, DW steps ahead);
+//    the token rows (x gathered through the sorted pair list, or act) are shared by all
+//    wavefronts and land in a second ring DA steps ahead.  Physical 16-byte chunk pc of LDS row
+//    r holds logical chunk pc ^ (r & 7) (applied on the global-address side of the copy), which
+//    keeps the 16-byte MFMA fragment reads free of bank conflicts.
 //  * v_mfma_f32_16x16x32_bf16 with the weights as the row operand: the accumulator of lane l
 //    holds 4 consecutive output columns of token l%16, so the epilogue applies
 //    act = silu(g) * u in registers and stores 8 bytes per lane.
-//  * One s_barrier per K step (64 elements) orders the LDS ring; outstanding-load counts are
-//    waited for explicitly so that a barrier never drains the weight prefetch queue.
+//  * One s_barrier per K step (64 elements) orders the token ring; outstanding-copy counts are
+//    waited for explicitly (s_waitcnt vmcnt(n)) so that a barrier never drains the copy queue.
 //  * Row blocks beyond the tile's real row count are skipped (the K loop is instantiated per
-//    row-block count), so an expert with 140 tokens costs 9 blocks of 16, not 256 rows.
+//    row-block count), so an expert with 140 tokens costs 9-10 blocks of 16, not 256 rows.
 //
 // Workgroups are numbered so that each XCD (own L2) gets a contiguous range of the
 // (expert tile, column slab) work: the token rows of an expert stay in one L2.
@@ -37,21 +38,14 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int GM_BK = 64;                 // k elements per step (one 128-byte LDS row per token row)
-constexpr int GM_WAVES = 8;
-constexpr int GM_THREADS = GM_WAVES * kWave;
 constexpr int GM_XCDS = 8;
-constexpr int GM_B_LOADS = 4;             // weight loads per lane per step: 2 blocks x 2 halves of the step
+constexpr int GM_W_COPIES = 4;            // weight copies per wavefront per step: 32 rows, 8 rows each
+constexpr int GM_W_STAGE = 32 * 128;      // bytes of one wavefront's weight stage
+constexpr int GM_CUS = 256;
 
 #define MOE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define MOE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define MOE_WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
-// 16-byte global load issued exactly here.  The compiler does not track its completion: the value
-// may only be read after an explicit s_waitcnt followed by a MOE_TIE_SET that names the register
-// (an empty asm that makes every later reader data-dependent on a point after the wait, so no
-// reader can be scheduled above it).
-#define MOE_LOAD16(reg, ptr, off) \
-    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(reg) : "v"(ptr), "n"(off) : "memory")
-#define MOE_TIE_SET(r0, r1, r2, r3) asm volatile("" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3)::"memory")
 
 __device__ __forceinline__ int lds_off(int row, int chunk)   // byte offset of logical 16-byte chunk of a row
 {
@@ -66,54 +60,79 @@ struct GemmArgs {
     int K, n_out, top_k;
 };
 
+// Compile-time shape of one kernel variant.
+//   MB_MAX  row blocks (of 16) a tile may have        NW  wavefronts per workgroup
+//   DA      token-row stages in flight                DW  weight stages in flight (DW >= DA)
+template <int MB_MAX_, int NW_, int DA_, int DW_, bool SWIGLU_>
+struct Shape {
+    static constexpr int MB_MAX = MB_MAX_, NW = NW_, DA = DA_, DW = DW_;
+    static constexpr bool SWIGLU = SWIGLU_;
+    static constexpr int THREADS = NW * kWave;
+    static constexpr int SLAB = SWIGLU ? 16 : 32;             // output columns per wavefront
+    static constexpr int COLS = SLAB * NW;                    // output columns per workgroup
+    static constexpr int STAGE_BYTES = MB_MAX * 16 * 128;     // one token-row stage
+    static constexpr int A_RING_BYTES = (DA + 1) * STAGE_BYTES;
+    static constexpr int LDS_BYTES = A_RING_BYTES + (DW + 1) * NW * GM_W_STAGE;
+    static_assert(DW >= DA && DA >= 1, "weights are copied at least as far ahead as token rows");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
+};
+
 // Everything after the (tile, column slab) decision, instantiated per active row-block count NB.
-template <int MB_MAX, int D, bool SWIGLU, int NB>
+template <class SH, int NB>
 __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, unsigned char *smem)
 {
-    constexpr int S = D + 1;                                  // register sets == LDS stages
-    constexpr int STAGE_BYTES = MB_MAX * 16 * 128;
-    constexpr int A_PASS_MAX = (MB_MAX * 2 + GM_WAVES - 1) / GM_WAVES;   // 8-row copy passes per wavefront
-    constexpr int SLAB = SWIGLU ? 16 : 32;                    // output columns per wavefront
+    constexpr int NW = SH::NW, DA = SH::DA, DW = SH::DW;
+    constexpr bool SWIGLU = SH::SWIGLU;
+    constexpr int SA = DA + 1;                                // token-row stages
+    constexpr int SW = DW + 1;                                // weight stages
+    constexpr int STAGE_BYTES = SH::STAGE_BYTES;
+    constexpr int A_PASS_MAX = (NB * 2 + NW - 1) / NW;        // 8-row copy passes per wavefront
+    constexpr int SLAB = SH::SLAB;
+    static_assert(A_PASS_MAX <= 8, "wait table below covers up to 8 copy passes per wavefront");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lets the compiler keep it scalar
     const int l16 = lane & 15, lq = lane >> 4;
+    const int crow = lane >> 3;                               // copy: row inside an 8-row pass
+    const int cchunk = ((lane & 7) ^ crow) << 3;              // copy: logical chunk (in elements) for this lane's slot
     const int rows = tile.rows;
     const int K = g.K, n_out = g.n_out;
     const int nk = K / GM_BK;
 
-    // ---- weight row pointers (two 16-row blocks per wavefront) ----------------
-    const int col0 = ct * (SLAB * GM_WAVES) + wave * SLAB;    // first output column of this wavefront
+    // ---- weight row pointers: copy q (0..3) moves rows 8q..8q+7 of this wavefront's 32 rows
+    // (rows 0..15 = first block, 16..31 = second block)
+    const int col0 = ct * SH::COLS + wave * SLAB;             // first output column of this wavefront
     const int w_rows = SWIGLU ? 2 * n_out : n_out;
-    int wrow0, wrow1;
-    if constexpr (SWIGLU) {
-        const int c = min(col0 + l16, n_out - 1);             // clamp: columns past the end are never stored
-        wrow0 = c;                                            // gate row
-        wrow1 = n_out + c;                                    // matching up row
-    } else {
-        wrow0 = min(col0 + l16, n_out - 1);
-        wrow1 = min(col0 + 16 + l16, n_out - 1);
+    const uint16_t *wbase = g.W + (size_t)tile.expert * w_rows * K + cchunk;
+    const uint16_t *w_ptr[GM_W_COPIES];
+#pragma unroll
+    for (int q = 0; q < GM_W_COPIES; ++q) {
+        const int in_blk = (q & 1) * 8 + crow;                // row inside the 16-row block
+        int wrow;
+        if constexpr (SWIGLU) {
+            const int c = min(col0 + in_blk, n_out - 1);      // clamp: columns past the end are never stored
+            wrow = (q < 2) ? c : n_out + c;                   // gate row / matching up row
+        } else {
+            wrow = min(col0 + (q >> 1) * 16 + in_blk, n_out - 1);
+        }
+        w_ptr[q] = wbase + (size_t)wrow * K;
     }
-    const uint16_t *wbase = g.W + (size_t)tile.expert * w_rows * K + lq * 8;
-    const uint16_t *wp0 = wbase + (size_t)wrow0 * K;
-    const uint16_t *wp1 = wbase + (size_t)wrow1 * K;
+    unsigned char *const w_ring = smem + SH::A_RING_BYTES + wave * (SW * GM_W_STAGE);
 
-    // ---- token row pointers for the global -> LDS copies -----------------------
-    // copy pass p moves LDS rows 8p..8p+7 (lane l: row 8p + l/8, physical chunk l%8)
-    const int rows16 = NB * 16;
+    // ---- token row pointers: copy pass p moves LDS rows 8p..8p+7 -----------------
     int a_cnt = 0;
     const uint16_t *a_ptr[A_PASS_MAX];
     int a_dst[A_PASS_MAX];
 #pragma unroll
     for (int i = 0; i < A_PASS_MAX; ++i) {
-        const int p = wave + GM_WAVES * i;
-        if (8 * p < rows16) ++a_cnt;
-        int r = 8 * p + (lane >> 3);
+        const int p = wave + NW * i;
+        if (8 * p < NB * 16) ++a_cnt;
+        int r = 8 * p + crow;
         r = r < rows ? r : rows - 1;                          // padded rows repeat the last row; never stored
         size_t src;
         if constexpr (SWIGLU) src = (size_t)(g.sorted_pair[tile.row0 + r] / g.top_k);
         else src = (size_t)(tile.row0 + r);
-        a_ptr[i] = g.A + src * K + (((lane & 7) ^ (lane >> 3)) << 3);
+        a_ptr[i] = g.A + src * K + cchunk;
         a_dst[i] = p * 1024;
     }
 
@@ -123,62 +142,72 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[m][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 wq[S][2][2];                                        // [set][block][half of the K step]
-
-    // issue the loads of K step `s` (clamped to the last step: the tail prefetches are dummies)
-#define MOE_ISSUE(s, set)                                                                              \
+    // Copies of K step `s`, clamped to the last step (the tail copies are dummies that keep the
+    // number of copies per slot constant, which the explicit wait counts rely on).
+#define MOE_COPY_TOKENS(s)                                                                             \
     {                                                                                                  \
         const int k0_ = min((s), nk - 1) * GM_BK;                                                      \
-        unsigned char *dst_ = smem + ((s) % S) * STAGE_BYTES;                                          \
+        unsigned char *dst_ = smem + ((s) % SA) * STAGE_BYTES;                                         \
         _Pragma("unroll") for (int i = 0; i < A_PASS_MAX; ++i)                                         \
             if (i < a_cnt)                                                                             \
                 __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(a_ptr[i] + k0_), MOE_LDS_PTR(dst_ + a_dst[i]), 16, 0, 0); \
-        MOE_LOAD16(wq[set][0][0], wp0 + k0_, 0);                                                       \
-        MOE_LOAD16(wq[set][0][1], wp0 + k0_, 64);                                                      \
-        MOE_LOAD16(wq[set][1][0], wp1 + k0_, 0);                                                       \
-        MOE_LOAD16(wq[set][1][1], wp1 + k0_, 64);                                                      \
+    }
+#define MOE_COPY_WEIGHTS(s)                                                                            \
+    {                                                                                                  \
+        const int k0_ = min((s), nk - 1) * GM_BK;                                                      \
+        unsigned char *dst_ = w_ring + ((s) % SW) * GM_W_STAGE;                                        \
+        _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                        \
+            __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(w_ptr[q] + k0_), MOE_LDS_PTR(dst_ + q * 1024), 16, 0, 0); \
     }
 
-    // prologue: D steps in flight
+    // Issue slot t (t = -DW .. nk-1) holds [token copy of step t+DA, weight copy of step t+DW].
+    // prologue: slots -DW .. -1
 #pragma unroll
-    for (int d = 0; d < D; ++d) MOE_ISSUE(d, d)
+    for (int t = -DW; t < 0; ++t) {
+        if (t + DA >= 0) MOE_COPY_TOKENS(t + DA)
+        MOE_COPY_WEIGHTS(t + DW)
+    }
 
-    for (int s0 = 0; s0 < nk; s0 += S) {
-#pragma unroll
-        for (int j = 0; j < S; ++j) {
-            const int s = s0 + j;
-            // Loads of step s (issued D slots ago) must have landed; the D-1 newer slots may stay
-            // in flight.  Every slot of this wavefront is GM_B_LOADS + a_cnt loads, returned in order.
-switch (a_cnt) {
-            case 0: MOE_WAIT_VMCNT((D - 1) * (GM_B_LOADS + 0)); break;
-            case 1: MOE_WAIT_VMCNT((D - 1) * (GM_B_LOADS + 1)); break;
-            case 2: MOE_WAIT_VMCNT((D - 1) * (GM_B_LOADS + 2)); break;
-            case 3: MOE_WAIT_VMCNT((D - 1) * (GM_B_LOADS + 3)); break;
-            default: MOE_WAIT_VMCNT((D - 1) * (GM_B_LOADS + 4)); break;
-            }
-            MOE_TIE_SET(wq[j][0][0], wq[j][0][1], wq[j][1][0], wq[j][1][1]);
-            asm volatile("s_barrier" ::: "memory");           // stage s complete for everyone; stage s-1 free
-            MOE_ISSUE(s + D, (j + D) % S)
-            __builtin_amdgcn_sched_barrier(0);
-            if (s < nk) {
-                const unsigned char *sa = smem + (s % S) * STAGE_BYTES;
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const bf16x8 w0 = __builtin_bit_cast(bf16x8, wq[j][0][kk]);
-                    const bf16x8 w1 = __builtin_bit_cast(bf16x8, wq[j][1][kk]);
-#pragma unroll
-                    for (int m = 0; m < NB; ++m) {
-                        const bf16x8 t = *reinterpret_cast<const bf16x8 *>(sa + lds_off(m * 16 + l16, kk * 4 + lq));
-                        acc[m][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, t, acc[m][0], 0, 0, 0);
-                        acc[m][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, t, acc[m][1], 0, 0, 0);
-                    }
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
+    for (int s = 0; s < nk; ++s) {
+        // Step s needs its token copy (slot s-DA) and its weight copy (slot s-DW, older or same)
+        // landed.  Copies complete in order, so it is enough to let only what was issued after the
+        // younger of the two stay in flight: DA-1 complete slots, plus (when the weights run
+        // further ahead than the token rows) the weight copies sharing the slot of that token copy.
+#define MOE_WAIT_FOR_STEP(a) MOE_WAIT_VMCNT((DW > DA ? GM_W_COPIES : 0) + (DA - 1) * (GM_W_COPIES + (a)))
+        switch (a_cnt) {
+        case 0: MOE_WAIT_FOR_STEP(0); break;
+        case 1: MOE_WAIT_FOR_STEP(1); break;
+        case 2: MOE_WAIT_FOR_STEP(2); break;
+        case 3: MOE_WAIT_FOR_STEP(3); break;
+        case 4: MOE_WAIT_FOR_STEP(4); break;
+        case 5: MOE_WAIT_FOR_STEP(5); break;
+        case 6: MOE_WAIT_FOR_STEP(6); break;
+        case 7: MOE_WAIT_FOR_STEP(7); break;
+        default: MOE_WAIT_FOR_STEP(8); break;
         }
+#undef MOE_WAIT_FOR_STEP
+        asm volatile("s_barrier" ::: "memory");               // token stage s complete for everyone; stage s-1 free
+        MOE_COPY_TOKENS(s + DA)
+        MOE_COPY_WEIGHTS(s + DW)
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char *sa = smem + (s % SA) * STAGE_BYTES;
+        const unsigned char *sw = w_ring + (s % SW) * GM_W_STAGE;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 w0 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(l16, kk * 4 + lq));
+            const bf16x8 w1 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(16 + l16, kk * 4 + lq));
+#pragma unroll
+            for (int m = 0; m < NB; ++m) {
+                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(sa + lds_off(m * 16 + l16, kk * 4 + lq));
+                acc[m][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, t, acc[m][0], 0, 0, 0);
+                acc[m][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, t, acc[m][1], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
-    MOE_WAIT_VMCNT(0);                                        // dummy tail prefetches must not outlive the LDS ring
-#undef MOE_ISSUE
+    MOE_WAIT_VMCNT(0);                                        // dummy tail copies must not outlive the LDS rings
+#undef MOE_COPY_TOKENS
+#undef MOE_COPY_WEIGHTS
 
     // ---- epilogue: lane l holds, for token l%16 of each row block, output columns 4*(l/16)..+3
     // of each of its two weight blocks
@@ -216,24 +245,24 @@ switch (a_cnt) {
     }
 }
 
-template <int MB_MAX, int D, bool SWIGLU, int NB>
+template <class SH, int NB>
 __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const moe_tile &tile, int ct,
                                                 unsigned char *smem)
 {
-    if constexpr (NB > MB_MAX) {
+    if constexpr (NB > SH::MB_MAX) {
         return;
     } else {
         // row-block counts are rounded up to even above 4 to bound the number of instantiations
         constexpr int NEXT = NB < 4 ? NB + 1 : NB + 2;
-        if (nb <= NB) gemm_tile<MB_MAX, D, SWIGLU, NB>(g, tile, ct, smem);
-        else dispatch_blocks<MB_MAX, D, SWIGLU, NEXT>(nb, g, tile, ct, smem);
+        if (nb <= NB) gemm_tile<SH, NB>(g, tile, ct, smem);
+        else dispatch_blocks<SH, NEXT>(nb, g, tile, ct, smem);
     }
 }
 
-template <int MB_MAX, int D, bool SWIGLU>
-__global__ __launch_bounds__(GM_THREADS) void grouped_gemm_bf16_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
-                                                                       const int32_t *__restrict__ ntiles,
-                                                                       int col_tiles)
+template <class SH>
+__global__ __launch_bounds__(SH::THREADS) void grouped_gemm_bf16_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
+                                                                        const int32_t *__restrict__ ntiles,
+                                                                        int col_tiles)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int total = *ntiles * col_tiles;
@@ -247,40 +276,59 @@ __global__ __launch_bounds__(GM_THREADS) void grouped_gemm_bf16_kernel(GemmArgs 
     const int ct = local / head.count;                         // column slab
     const moe_tile tile = tiles[head.first + local % head.count];
     const int nb = ceil_div(tile.rows, 16);
-    dispatch_blocks<MB_MAX, D, SWIGLU, 1>(nb, g, tile, ct, smem);
+    dispatch_blocks<SH, 1>(nb, g, tile, ct, smem);
 }
 
-template <int MB_MAX, int D, bool SWIGLU>
-int launch_variant(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles, int max_tiles, hipStream_t s)
+template <class SH>
+int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles, int max_tiles, hipStream_t s)
 {
-    constexpr int cols_per_wg = (SWIGLU ? 16 : 32) * GM_WAVES;
-    const int col_tiles = ceil_div(g.n_out, cols_per_wg);
+    const int col_tiles = ceil_div(g.n_out, SH::COLS);
     const int blocks = ceil_div(max_tiles * col_tiles, GM_XCDS) * GM_XCDS;
-    const size_t lds = (size_t)(D + 1) * MB_MAX * 16 * 128;
-    auto kern = grouped_gemm_bf16_kernel<MB_MAX, D, SWIGLU>;
+    auto kern = grouped_gemm_bf16_kernel<SH>;
     static bool attr_done = false;          // raise the dynamic-LDS limit once per variant
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
         if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(GM_THREADS), lds, s, g, tiles, ntiles, col_tiles);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, ntiles, col_tiles);
     return check_launch();
+}
+
+// Narrow (4-wavefront) workgroups when the wide ones would leave compute units without work.
+template <int MB_MAX, bool SWIGLU>
+int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles, int max_tiles, int est_tiles,
+                    hipStream_t s)
+{
+    constexpr int DA = MB_MAX >= 16 ? 1 : 2;                  // 16 row blocks: 32 KiB per token stage
+    using Wide = Shape<MB_MAX, 8, DA, 2, SWIGLU>;
+    using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU>;
+    const long wide_wgs = (long)est_tiles * ceil_div(g.n_out, Wide::COLS);
+    if (wide_wgs < 2 * GM_CUS) return launch_shape<Narrow>(g, tiles, ntiles, max_tiles, s);
+    return launch_shape<Wide>(g, tiles, ntiles, max_tiles, s);
 }
 
 template <bool SWIGLU>
 int launch_by_tile_rows(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles,
-                        int max_tiles, hipStream_t s)
+                        int max_tiles, int est_tiles, hipStream_t s)
 {
     switch (tile_rows) {
-    case 256: return launch_variant<16, 3, SWIGLU>(g, tiles, ntiles, max_tiles, s);
-    case 128: return launch_variant<8, 3, SWIGLU>(g, tiles, ntiles, max_tiles, s);
-    case 64:  return launch_variant<4, 3, SWIGLU>(g, tiles, ntiles, max_tiles, s);
-    case 32:  return launch_variant<2, 3, SWIGLU>(g, tiles, ntiles, max_tiles, s);
-    case 16:  return launch_variant<1, 3, SWIGLU>(g, tiles, ntiles, max_tiles, s);
+    case 256: return launch_for_rows<16, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 128: return launch_for_rows<8, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 64:  return launch_for_rows<4, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 32:  return launch_for_rows<2, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 16:  return launch_for_rows<1, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
     default:  return MOE_ERR_UNSUPPORTED;
     }
+}
+
+// Tiles a balanced router is expected to produce (host-side estimate used only to pick the
+// workgroup width; the kernels read the real count from device memory).
+int expected_tiles(const moe_config &c)
+{
+    const long pairs = (long)c.T * c.top_k;
+    return (int)(pairs < c.E ? pairs : c.E);
 }
 
 }  // namespace
@@ -292,7 +340,7 @@ int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const 
     if (c.dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
     GemmArgs g{static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w1), sorted_pair,
                static_cast<uint16_t *>(act), c.H, c.I, c.top_k};
-    return launch_by_tile_rows<true>(tile_rows, g, tiles, ntiles, max_tiles, s);
+    return launch_by_tile_rows<true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
 }
 
 int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const void *act, const float *,
@@ -302,7 +350,7 @@ int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const vo
     if (c.dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
     GemmArgs g{static_cast<const uint16_t *>(act), static_cast<const uint16_t *>(w2), nullptr,
                static_cast<uint16_t *>(y), c.I, c.H, c.top_k};
-    return launch_by_tile_rows<false>(tile_rows, g, tiles, ntiles, max_tiles, s);
+    return launch_by_tile_rows<false>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
 }
 
 }  // namespace moe
