@@ -54,6 +54,23 @@ class HipEvents:
             self.hip.hipEventDestroy(ev)
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the gate/up GEMM from the committed counter summary, or None when
+    the kernel source has changed since the counters were taken (or none were taken)."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    src = os.path.join(ROOT, "paper_2602_19128_amd", "csrc", "moe_gemm.hip")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        doc = json.load(f)
+    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    rec = doc.get(workload)
+    if not rec or rec.get("moe_gemm_sha256") != sha:
+        return None
+    return {"fetch_bytes": rec["fetch_bytes"], "write_bytes": rec["write_bytes"], "unit": "bytes per launch"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +79,9 @@ def main():
     ap.add_argument("--workload", default="mixtral_prefill")
     ap.add_argument("--tokens", type=int, default=0,
                     help="override the workload's token count (supplementary points; not the headline config)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, used to scale "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
                     help="CPU work budget for the oracle sample; 0 skips the CPU baseline")
@@ -89,6 +109,13 @@ def main():
     ws = torch.empty((moe.moe_workspace_size(cfg),), dtype=torch.uint8, device=dev)
     call = lambda ev=None: moe.moe_forward(cfg, inp.x, inp.x_scale, inp.router_w, inp.bias, inp.w1, inp.w1_scale,
                                            inp.w2, inp.w2_scale, out=out, workspace=ws, events=ev)
+
+    if args.copy_calibration:
+        src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)          # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     hip = HipEvents()
     K, W = args.steps, args.warmup
@@ -135,7 +162,7 @@ def main():
     g1_gbps = g1_bytes / g1_sec / 1e9
     roofline = {"kernel": "grouped_gemm_swiglu", "bound": "hbm", "achieved": round(g1_gbps, 1),
                 "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g1_gbps / PEAK_HBM_GBPS, 4),
-                "traffic": None, "bytes_per_launch": int(g1_bytes), "avg_launch_us": round(g1_sec * 1e6, 2),
+                "traffic": measured_traffic(wl.name), "bytes_per_launch": int(g1_bytes), "avg_launch_us": round(g1_sec * 1e6, 2),
                 "tflops": round(4.0 * H * I * P / g1_sec / 1e12, 1),
                 "frac_mfma": round(4.0 * H * I * P / g1_sec / 1e12 / PEAK_MFMA_TFLOPS[kind], 4)}
 
