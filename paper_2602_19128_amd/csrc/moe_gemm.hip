@@ -1,6 +1,7 @@
-// Grouped expert GEMMs on the bf16 matrix cores (paper Sec. 4.5 "Expert FFN
-// computation": tensor-core tiles, loads of the next block overlapping the compute of the
-// current one, experts without tokens skipped).
+// Grouped expert GEMMs on the matrix cores, bf16 and block-scaled fp8 (paper Sec. 4.5 "Expert
+// FFN computation": tensor-core tiles, loads of the next block overlapping the compute of the
+// current one, experts without tokens skipped; the kernel table of Sec. 4.3 names fp8 packing and
+// scaling as the challenge of this operator).
 //
 // Both GEMMs are C[m,n] = sum_k A[m,k] * W[e,n,k] with few rows m per expert (a few to a
 // few hundred) against large weight matrices, so the weights must stream from HBM exactly
@@ -18,11 +19,19 @@
 //    wavefronts and land in a second ring DA steps ahead.  Physical 16-byte chunk pc of LDS row
 //    r holds logical chunk pc ^ (r & 7) (applied on the global-address side of the copy), which
 //    keeps the 16-byte MFMA fragment reads free of bank conflicts.
-//  * v_mfma_f32_16x16x32_bf16 with the weights as the row operand: the accumulator of lane l
-//    holds 4 consecutive output columns of token l%16, so the epilogue applies
-//    act = silu(g) * u in registers and stores 8 bytes per lane.
-//  * One s_barrier per K step (64 elements) orders the token ring; outstanding-copy counts are
-//    waited for explicitly (s_waitcnt vmcnt(n)) so that a barrier never drains the copy queue.
+//  * One K step is 128 bytes of every row: 64 bf16 elements (two v_mfma_f32_16x16x32_bf16) or
+//    128 fp8 elements (one v_mfma_f32_16x16x128_f8f6f4, exactly one 128-wide scale block).  The
+//    weights are the row operand, so the accumulator of lane l holds 4 consecutive output
+//    columns of token l%16: the epilogue applies act = silu(g) * u in registers and stores whole
+//    8-byte (bf16) or 4-byte (fp8) pieces.
+//  * fp8: each K step's product is formed in a fresh accumulator and folded into the running
+//    fp32 sum with (activation scale of the token's 1x128 block) x (weight scale of the 128x128
+//    block).  Activation scales ride along with the token rows in the LDS ring; a wavefront's
+//    weight scales for the whole K range sit in one or two registers and are broadcast by lane
+//    index.  The gate/up epilogue re-quantises act per 1x128 block (scale = amax/448) - a
+//    workgroup of 8 wavefronts covers exactly one such block per row.
+//  * One s_barrier per K step orders the token ring; outstanding-copy counts are waited for
+//    explicitly (s_waitcnt vmcnt(n)) so that a barrier never drains the copy queue.
 //  * Row blocks beyond the tile's real row count are skipped (the K loop is instantiated per
 //    row-block count), so an expert with 140 tokens costs 9-10 blocks of 16, not 256 rows.
 //
@@ -36,12 +45,14 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
-constexpr int GM_BK = 64;                 // k elements per step (one 128-byte LDS row per token row)
+constexpr int GM_STEP_BYTES = 128;        // bytes of every row consumed per K step
 constexpr int GM_XCDS = 8;
 constexpr int GM_W_COPIES = 4;            // weight copies per wavefront per step: 32 rows, 8 rows each
 constexpr int GM_W_STAGE = 32 * 128;      // bytes of one wavefront's weight stage
 constexpr int GM_CUS = 256;
+constexpr float GM_FP8_MAX = 448.f;
 
 #define MOE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define MOE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -53,28 +64,35 @@ __device__ __forceinline__ int lds_off(int row, int chunk)   // byte offset of l
 }
 
 struct GemmArgs {
-    const uint16_t *A;            // gate/up: x [T,K]; down: act [P,K]
-    const uint16_t *W;            // [E, w_rows, K]
+    const unsigned char *A;       // gate/up: x [T,K]; down: act [P,K]
+    const float *a_scale;         // fp8: [T or P, K/128]
+    const unsigned char *W;       // [E, w_rows, K]
+    const float *w_scale;         // fp8: [E, w_rows/128, K/128]
     const int32_t *sorted_pair;   // gate/up only
-    uint16_t *out;                // gate/up: act [P,n_out]; down: y [P,n_out]
+    unsigned char *out;           // gate/up: act [P,n_out] (bf16 / fp8); down: y [P,n_out] bf16
+    float *out_scale;             // fp8 gate/up: act_scale [P, n_out/128]
     int K, n_out, top_k;
 };
 
 // Compile-time shape of one kernel variant.
 //   MB_MAX  row blocks (of 16) a tile may have        NW  wavefronts per workgroup
 //   DA      token-row stages in flight                DW  weight stages in flight (DW >= DA)
-template <int MB_MAX_, int NW_, int DA_, int DW_, bool SWIGLU_>
+template <int MB_MAX_, int NW_, int DA_, int DW_, bool SWIGLU_, bool FP8_>
 struct Shape {
     static constexpr int MB_MAX = MB_MAX_, NW = NW_, DA = DA_, DW = DW_;
-    static constexpr bool SWIGLU = SWIGLU_;
+    static constexpr bool SWIGLU = SWIGLU_, FP8 = FP8_;
     static constexpr int THREADS = NW * kWave;
     static constexpr int SLAB = SWIGLU ? 16 : 32;             // output columns per wavefront
     static constexpr int COLS = SLAB * NW;                    // output columns per workgroup
     static constexpr int STAGE_BYTES = MB_MAX * 16 * 128;     // one token-row stage
     static constexpr int A_RING_BYTES = (DA + 1) * STAGE_BYTES;
-    static constexpr int LDS_BYTES = A_RING_BYTES + (DW + 1) * NW * GM_W_STAGE;
+    static constexpr int W_RING_BYTES = (DW + 1) * NW * GM_W_STAGE;
+    // one fp32 activation scale per token row, copied 64 rows (one wavefront) at a time
+    static constexpr int SC_STAGE_BYTES = FP8 ? ((MB_MAX * 16 + 63) / 64) * 256 : 0;
+    static constexpr int LDS_BYTES = A_RING_BYTES + W_RING_BYTES + (DA + 1) * SC_STAGE_BYTES;
     static_assert(DW >= DA && DA >= 1, "weights are copied at least as far ahead as token rows");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
+    static_assert(!(FP8 && SWIGLU) || COLS == kQBlock, "fp8 gate/up: a workgroup re-quantises one 1x128 block per row");
 };
 
 // Everything after the (tile, column slab) decision, instantiated per active row-block count NB.
@@ -82,29 +100,31 @@ template <class SH, int NB>
 __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, unsigned char *smem)
 {
     constexpr int NW = SH::NW, DA = SH::DA, DW = SH::DW;
-    constexpr bool SWIGLU = SH::SWIGLU;
+    constexpr bool SWIGLU = SH::SWIGLU, FP8 = SH::FP8;
+    constexpr int ES = FP8 ? 1 : 2;                           // bytes per element
     constexpr int SA = DA + 1;                                // token-row stages
     constexpr int SW = DW + 1;                                // weight stages
     constexpr int STAGE_BYTES = SH::STAGE_BYTES;
     constexpr int A_PASS_MAX = (NB * 2 + NW - 1) / NW;        // 8-row copy passes per wavefront
     constexpr int SLAB = SH::SLAB;
-    static_assert(A_PASS_MAX <= 8, "wait table below covers up to 8 copy passes per wavefront");
+    static_assert(A_PASS_MAX <= 8, "wait table below covers up to 9 extra copies per wavefront");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lets the compiler keep it scalar
     const int l16 = lane & 15, lq = lane >> 4;
     const int crow = lane >> 3;                               // copy: row inside an 8-row pass
-    const int cchunk = ((lane & 7) ^ crow) << 3;              // copy: logical chunk (in elements) for this lane's slot
+    const int cbyte = ((lane & 7) ^ crow) << 4;               // copy: byte offset of the logical chunk for this lane's slot
     const int rows = tile.rows;
-    const int K = g.K, n_out = g.n_out;
-    const int nk = K / GM_BK;
+    const int n_out = g.n_out;
+    const size_t row_bytes = (size_t)g.K * ES;
+    const int nk = (int)(row_bytes / GM_STEP_BYTES);
 
     // ---- weight row pointers: copy q (0..3) moves rows 8q..8q+7 of this wavefront's 32 rows
     // (rows 0..15 = first block, 16..31 = second block)
     const int col0 = ct * SH::COLS + wave * SLAB;             // first output column of this wavefront
     const int w_rows = SWIGLU ? 2 * n_out : n_out;
-    const uint16_t *wbase = g.W + (size_t)tile.expert * w_rows * K + cchunk;
-    const uint16_t *w_ptr[GM_W_COPIES];
+    const unsigned char *wbase = g.W + (size_t)tile.expert * w_rows * row_bytes + cbyte;
+    const unsigned char *w_ptr[GM_W_COPIES];
 #pragma unroll
     for (int q = 0; q < GM_W_COPIES; ++q) {
         const int in_blk = (q & 1) * 8 + crow;                // row inside the 16-row block
@@ -115,13 +135,25 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         } else {
             wrow = min(col0 + (q >> 1) * 16 + in_blk, n_out - 1);
         }
-        w_ptr[q] = wbase + (size_t)wrow * K;
+        w_ptr[q] = wbase + (size_t)wrow * row_bytes;
     }
     unsigned char *const w_ring = smem + SH::A_RING_BYTES + wave * (SW * GM_W_STAGE);
+    unsigned char *const sc_ring = smem + SH::A_RING_BYTES + SH::W_RING_BYTES;
+
+    // fp8: this wavefront's weight scales for every K step, lane l holds step l (and l + 64)
+    float wsc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+    if constexpr (FP8) {
+        const int cc = min(col0, n_out - 1);
+        const int blk0 = cc / kQBlock;
+        const int blk1 = SWIGLU ? (n_out + cc) / kQBlock : blk0;
+        const float *ws = g.w_scale + (size_t)tile.expert * (w_rows / kQBlock) * nk;
+        if (lane < nk) { wsc[0][0] = ws[(size_t)blk0 * nk + lane]; wsc[1][0] = ws[(size_t)blk1 * nk + lane]; }
+        if (lane + 64 < nk) { wsc[0][1] = ws[(size_t)blk0 * nk + lane + 64]; wsc[1][1] = ws[(size_t)blk1 * nk + lane + 64]; }
+    }
 
     // ---- token row pointers: copy pass p moves LDS rows 8p..8p+7 -----------------
-    int a_cnt = 0;
-    const uint16_t *a_ptr[A_PASS_MAX];
+    int a_cnt = 0;                                            // copies per slot beyond the weight copies
+    const unsigned char *a_ptr[A_PASS_MAX];
     int a_dst[A_PASS_MAX];
 #pragma unroll
     for (int i = 0; i < A_PASS_MAX; ++i) {
@@ -132,8 +164,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         size_t src;
         if constexpr (SWIGLU) src = (size_t)(g.sorted_pair[tile.row0 + r] / g.top_k);
         else src = (size_t)(tile.row0 + r);
-        a_ptr[i] = g.A + src * K + cchunk;
+        a_ptr[i] = g.A + src * row_bytes + cbyte;
         a_dst[i] = p * 1024;
+    }
+    // fp8: wavefront j also copies the activation scales of rows 64j..64j+63 (4 bytes per lane)
+    const float *sc_ptr = nullptr;
+    bool sc_copy = false;
+    if constexpr (FP8) {
+        sc_copy = wave * 64 < NB * 16;
+        if (sc_copy) ++a_cnt;
+        int r = wave * 64 + lane;
+        r = r < rows ? r : rows - 1;
+        size_t src;
+        if constexpr (SWIGLU) src = (size_t)(g.sorted_pair[tile.row0 + r] / g.top_k);
+        else src = (size_t)(tile.row0 + r);
+        sc_ptr = g.a_scale + src * nk;
     }
 
     f32x4 acc[NB][2];
@@ -146,15 +191,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     // number of copies per slot constant, which the explicit wait counts rely on).
 #define MOE_COPY_TOKENS(s)                                                                             \
     {                                                                                                  \
-        const int k0_ = min((s), nk - 1) * GM_BK;                                                      \
+        const int ks_ = min((s), nk - 1);                                                              \
+        const int k0_ = ks_ * GM_STEP_BYTES;                                                           \
         unsigned char *dst_ = smem + ((s) % SA) * STAGE_BYTES;                                         \
         _Pragma("unroll") for (int i = 0; i < A_PASS_MAX; ++i)                                         \
-            if (i < a_cnt)                                                                             \
+            if (i < a_cnt - (sc_copy ? 1 : 0))                                                         \
                 __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(a_ptr[i] + k0_), MOE_LDS_PTR(dst_ + a_dst[i]), 16, 0, 0); \
+        if constexpr (FP8) {                                                                           \
+            if (sc_copy)                                                                               \
+                __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(sc_ptr + ks_),                         \
+                                                 MOE_LDS_PTR(sc_ring + ((s) % SA) * SH::SC_STAGE_BYTES + wave * 256), 4, 0, 0); \
+        }                                                                                              \
     }
 #define MOE_COPY_WEIGHTS(s)                                                                            \
     {                                                                                                  \
-        const int k0_ = min((s), nk - 1) * GM_BK;                                                      \
+        const int k0_ = min((s), nk - 1) * GM_STEP_BYTES;                                              \
         unsigned char *dst_ = w_ring + ((s) % SW) * GM_W_STAGE;                                        \
         _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                        \
             __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(w_ptr[q] + k0_), MOE_LDS_PTR(dst_ + q * 1024), 16, 0, 0); \
@@ -183,7 +234,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         case 5: MOE_WAIT_FOR_STEP(5); break;
         case 6: MOE_WAIT_FOR_STEP(6); break;
         case 7: MOE_WAIT_FOR_STEP(7); break;
-        default: MOE_WAIT_FOR_STEP(8); break;
+        case 8: MOE_WAIT_FOR_STEP(8); break;
+        default: MOE_WAIT_FOR_STEP(9); break;
         }
 #undef MOE_WAIT_FOR_STEP
         asm volatile("s_barrier" ::: "memory");               // token stage s complete for everyone; stage s-1 free
@@ -192,15 +244,51 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sa = smem + (s % SA) * STAGE_BYTES;
         const unsigned char *sw = w_ring + (s % SW) * GM_W_STAGE;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 w0 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(l16, kk * 4 + lq));
-            const bf16x8 w1 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(16 + l16, kk * 4 + lq));
+        if constexpr (FP8) {
+            // one MFMA spans the whole step: lane (l16, lq) holds bytes 32*lq .. 32*lq+31 of its row
+            const float *ssc = reinterpret_cast<const float *>(sc_ring + (s % SA) * SH::SC_STAGE_BYTES);
+            const int sl = s & 63;
+            const float sw0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(
+                __builtin_bit_cast(int, s < 64 ? wsc[0][0] : wsc[0][1]), sl));
+            const float sw1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(
+                __builtin_bit_cast(int, s < 64 ? wsc[1][0] : wsc[1][1]), sl));
+            i32x8 w0, w1;
+            {
+                const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(sw + lds_off(l16, 2 * lq));
+                const u32x4 hi0 = *reinterpret_cast<const u32x4 *>(sw + lds_off(l16, 2 * lq + 1));
+                const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(sw + lds_off(16 + l16, 2 * lq));
+                const u32x4 hi1 = *reinterpret_cast<const u32x4 *>(sw + lds_off(16 + l16, 2 * lq + 1));
+                w0 = i32x8{(int)lo0.x, (int)lo0.y, (int)lo0.z, (int)lo0.w, (int)hi0.x, (int)hi0.y, (int)hi0.z, (int)hi0.w};
+                w1 = i32x8{(int)lo1.x, (int)lo1.y, (int)lo1.z, (int)lo1.w, (int)hi1.x, (int)hi1.y, (int)hi1.z, (int)hi1.w};
+            }
 #pragma unroll
             for (int m = 0; m < NB; ++m) {
-                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(sa + lds_off(m * 16 + l16, kk * 4 + lq));
-                acc[m][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, t, acc[m][0], 0, 0, 0);
-                acc[m][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, t, acc[m][1], 0, 0, 0);
+                const u32x4 lo = *reinterpret_cast<const u32x4 *>(sa + lds_off(m * 16 + l16, 2 * lq));
+                const u32x4 hi = *reinterpret_cast<const u32x4 *>(sa + lds_off(m * 16 + l16, 2 * lq + 1));
+                const i32x8 t = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+                const float sx = ssc[m * 16 + l16];
+                const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+                // e4m3 x e4m3, hardware block scales set to 1.0 (E8M0 0x7f): the fp32 scales are applied below
+                const f32x4 p0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w0, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                const f32x4 p1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w1, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                const float f0 = sx * sw0, f1 = sx * sw1;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    acc[m][0][v] = fmaf(p0[v], f0, acc[m][0][v]);
+                    acc[m][1][v] = fmaf(p1[v], f1, acc[m][1][v]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const bf16x8 w0 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(l16, kk * 4 + lq));
+                const bf16x8 w1 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(16 + l16, kk * 4 + lq));
+#pragma unroll
+                for (int m = 0; m < NB; ++m) {
+                    const bf16x8 t = *reinterpret_cast<const bf16x8 *>(sa + lds_off(m * 16 + l16, kk * 4 + lq));
+                    acc[m][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, t, acc[m][0], 0, 0, 0);
+                    acc[m][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, t, acc[m][1], 0, 0, 0);
+                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -211,34 +299,74 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 
     // ---- epilogue: lane l holds, for token l%16 of each row block, output columns 4*(l/16)..+3
     // of each of its two weight blocks
+    if constexpr (SWIGLU && FP8) {
+        // act = silu(g)*u, then per-row amax over the workgroup's 128 columns -> scale = amax/448
+        float a[NB][4];
+        float *red = reinterpret_cast<float *>(smem);         // [NW][NB*16], reuses the token ring
+        __syncthreads();                                      // every wavefront is done with the rings
 #pragma unroll
-    for (int m = 0; m < NB; ++m) {
-        const int r = m * 16 + l16;
-        if (r >= rows) continue;
-        uint16_t *orow = g.out + (size_t)(tile.row0 + r) * n_out;
-        if constexpr (SWIGLU) {
-            const int c = col0 + lq * 4;
-            if (c < n_out) {
-                float a[4];
+        for (int m = 0; m < NB; ++m) {
+            float mx = 0.f;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float gt = acc[m][0][v], up = acc[m][1][v];
-                    a[v] = gt / (1.f + __expf(-gt)) * up;
-                }
-                uint2 o;
-                o.x = pack_bf16x2(a[0], a[1]);
-                o.y = pack_bf16x2(a[2], a[3]);
-                *reinterpret_cast<uint2 *>(orow + c) = o;
+            for (int v = 0; v < 4; ++v) {
+                const float gt = acc[m][0][v], up = acc[m][1][v];
+                a[m][v] = (col0 + lq * 4 + v < n_out) ? gt / (1.f + __expf(-gt)) * up : 0.f;
+                mx = fmaxf(mx, fabsf(a[m][v]));
             }
-        } else {
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            if (lq == 0) red[wave * (NB * 16) + m * 16 + l16] = mx;
+        }
+        __syncthreads();
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const int c = col0 + b * 16 + lq * 4;
+        for (int m = 0; m < NB; ++m) {
+            const int r = m * 16 + l16;
+            float amax = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < NW; ++wv) amax = fmaxf(amax, red[wv * (NB * 16) + r]);
+            if (r >= rows) continue;
+            const float scale = amax > 0.f ? amax / GM_FP8_MAX : 1.f;
+            const float inv = 1.f / scale;
+            float q[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) q[v] = fminf(fmaxf(a[m][v] * inv, -GM_FP8_MAX), GM_FP8_MAX);
+            int packed = 0;
+            packed = __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], packed, false);
+            packed = __builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], packed, true);
+            const int c = col0 + lq * 4;
+            if (c < n_out) *reinterpret_cast<int *>(g.out + (size_t)(tile.row0 + r) * n_out + c) = packed;
+            if (wave == 0 && lq == 0) g.out_scale[(size_t)(tile.row0 + r) * (n_out / kQBlock) + ct] = scale;
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < NB; ++m) {
+            const int r = m * 16 + l16;
+            if (r >= rows) continue;
+            uint16_t *orow = reinterpret_cast<uint16_t *>(g.out) + (size_t)(tile.row0 + r) * n_out;
+            if constexpr (SWIGLU) {
+                const int c = col0 + lq * 4;
                 if (c < n_out) {
+                    float a[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float gt = acc[m][0][v], up = acc[m][1][v];
+                        a[v] = gt / (1.f + __expf(-gt)) * up;
+                    }
                     uint2 o;
-                    o.x = pack_bf16x2(acc[m][b][0], acc[m][b][1]);
-                    o.y = pack_bf16x2(acc[m][b][2], acc[m][b][3]);
+                    o.x = pack_bf16x2(a[0], a[1]);
+                    o.y = pack_bf16x2(a[2], a[3]);
                     *reinterpret_cast<uint2 *>(orow + c) = o;
+                }
+            } else {
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    const int c = col0 + b * 16 + lq * 4;
+                    if (c < n_out) {
+                        uint2 o;
+                        o.x = pack_bf16x2(acc[m][b][0], acc[m][b][1]);
+                        o.y = pack_bf16x2(acc[m][b][2], acc[m][b][3]);
+                        *reinterpret_cast<uint2 *>(orow + c) = o;
+                    }
                 }
             }
         }
@@ -260,9 +388,8 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
 }
 
 template <class SH>
-__global__ __launch_bounds__(SH::THREADS) void grouped_gemm_bf16_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
-                                                                        const int32_t *__restrict__ ntiles,
-                                                                        int col_tiles)
+__global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
+                                                                   const int32_t *__restrict__ ntiles, int col_tiles)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int total = *ntiles * col_tiles;
@@ -284,7 +411,7 @@ int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles
 {
     const int col_tiles = ceil_div(g.n_out, SH::COLS);
     const int blocks = ceil_div(max_tiles * col_tiles, GM_XCDS) * GM_XCDS;
-    auto kern = grouped_gemm_bf16_kernel<SH>;
+    auto kern = grouped_gemm_kernel<SH>;
     static bool attr_done = false;          // raise the dynamic-LDS limit once per variant
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -296,29 +423,33 @@ int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles
     return check_launch();
 }
 
-// Narrow (4-wavefront) workgroups when the wide ones would leave compute units without work.
-template <int MB_MAX, bool SWIGLU>
+// Narrow (4-wavefront) workgroups when the wide ones would leave compute units without work
+// (not for the fp8 gate/up GEMM, whose epilogue needs a whole 128-column block per workgroup).
+template <int MB_MAX, bool SWIGLU, bool FP8>
 int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles, int max_tiles, int est_tiles,
                     hipStream_t s)
 {
     constexpr int DA = MB_MAX >= 16 ? 1 : 2;                  // 16 row blocks: 32 KiB per token stage
-    using Wide = Shape<MB_MAX, 8, DA, 2, SWIGLU>;
-    using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU>;
-    const long wide_wgs = (long)est_tiles * ceil_div(g.n_out, Wide::COLS);
-    if (wide_wgs < 2 * GM_CUS) return launch_shape<Narrow>(g, tiles, ntiles, max_tiles, s);
+    constexpr int DW = (MB_MAX >= 16 && FP8) ? 1 : 2;         // the scale ring of the largest fp8 tile needs the room
+    using Wide = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8>;
+    if constexpr (!(FP8 && SWIGLU)) {
+        using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU, FP8>;
+        const long wide_wgs = (long)est_tiles * ceil_div(g.n_out, Wide::COLS);
+        if (wide_wgs < 2 * GM_CUS) return launch_shape<Narrow>(g, tiles, ntiles, max_tiles, s);
+    }
     return launch_shape<Wide>(g, tiles, ntiles, max_tiles, s);
 }
 
-template <bool SWIGLU>
+template <bool SWIGLU, bool FP8>
 int launch_by_tile_rows(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles,
                         int max_tiles, int est_tiles, hipStream_t s)
 {
     switch (tile_rows) {
-    case 256: return launch_for_rows<16, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 128: return launch_for_rows<8, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 64:  return launch_for_rows<4, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 32:  return launch_for_rows<2, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 16:  return launch_for_rows<1, SWIGLU>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 256: return launch_for_rows<16, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 128: return launch_for_rows<8, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 64:  return launch_for_rows<4, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 32:  return launch_for_rows<2, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 16:  return launch_for_rows<1, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
     default:  return MOE_ERR_UNSUPPORTED;
     }
 }
@@ -334,23 +465,29 @@ int expected_tiles(const moe_config &c)
 }  // namespace
 
 int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const void *x,
-                       const float *, const void *w1, const float *, const int32_t *sorted_pair,
-                       const moe_tile *tiles, const int32_t *ntiles, void *act, float *, hipStream_t s)
+                       const float *x_scale, const void *w1, const float *w1_scale, const int32_t *sorted_pair,
+                       const moe_tile *tiles, const int32_t *ntiles, void *act, float *act_scale, hipStream_t s)
 {
-    if (c.dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
-    GemmArgs g{static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w1), sorted_pair,
-               static_cast<uint16_t *>(act), c.H, c.I, c.top_k};
-    return launch_by_tile_rows<true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+    GemmArgs g{static_cast<const unsigned char *>(x), x_scale, static_cast<const unsigned char *>(w1), w1_scale,
+               sorted_pair, static_cast<unsigned char *>(act), act_scale, c.H, c.I, c.top_k};
+    if (c.dtype == MOE_DTYPE_FP8_E4M3) {
+        if (c.H > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;  // weight scales of one slab sit in two registers
+        return launch_by_tile_rows<true, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+    }
+    return launch_by_tile_rows<true, false>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
 }
 
-int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const void *act, const float *,
-                     const void *w2, const float *, const moe_tile *tiles, const int32_t *ntiles, void *y,
+int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const void *act, const float *act_scale,
+                     const void *w2, const float *w2_scale, const moe_tile *tiles, const int32_t *ntiles, void *y,
                      hipStream_t s)
 {
-    if (c.dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
-    GemmArgs g{static_cast<const uint16_t *>(act), static_cast<const uint16_t *>(w2), nullptr,
-               static_cast<uint16_t *>(y), c.I, c.H, c.top_k};
-    return launch_by_tile_rows<false>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+    GemmArgs g{static_cast<const unsigned char *>(act), act_scale, static_cast<const unsigned char *>(w2), w2_scale,
+               nullptr, static_cast<unsigned char *>(y), nullptr, c.I, c.H, c.top_k};
+    if (c.dtype == MOE_DTYPE_FP8_E4M3) {
+        if (c.I > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;
+        return launch_by_tile_rows<false, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+    }
+    return launch_by_tile_rows<false, false>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
 }
 
 }  // namespace moe

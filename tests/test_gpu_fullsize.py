@@ -86,3 +86,8 @@ def test_dsv3_full_size(dsv3, name):
     gpu = base if name == "dsv3_prefill" else syn.make_inputs(syn.WORKLOADS[name], seed=0, device="cuda",
                                                                weights_from=base)
     _check_workload(gpu, host_w)
+
+
+def test_fp8_prefill_full_size():
+    gpu = syn.make_inputs(syn.WORKLOADS["fp8_prefill"], seed=0, device="cuda")
+    _check_workload(gpu, gpu.to("cpu"))

@@ -30,6 +30,11 @@ CASES = {
     "one_token": syn.Workload("one_token", T=1, H=128, I=64, E=8, top_k=3),
     "one_expert": syn.Workload("one_expert", T=40, H=128, I=64, E=1, top_k=1),
     "all_experts": syn.Workload("all_experts", T=24, H=128, I=64, E=4, top_k=4),
+    # fp8 e4m3 payload with 1x128 / 128x128 fp32 block scales
+    "fp8_small": syn.Workload("fp8_small", T=150, H=256, I=256, E=8, top_k=2, fp8=True),
+    "fp8_grouped": syn.Workload("fp8_grouped", T=96, H=512, I=256, E=256, top_k=8, n_group=8,
+                                topk_group=4, fp8=True, **GROUPED),
+    "fp8_tall": syn.Workload("fp8_tall", T=700, H=384, I=128, E=4, top_k=2, fp8=True),   # several 256-row tiles
 }
 
 
@@ -75,22 +80,38 @@ def _staged(case):
     return wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv
 
 
+def _act_f64(act, scale):
+    """Activations as the GPU stored them (bf16, or fp8 payload x 1x128 scale) in float64."""
+    a = f64(act)
+    if scale is not None:
+        a = a * np.repeat(f64(scale), 128, axis=1)
+    return a
+
+
 def test_gemm_swiglu(case):
     wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
-    act_g, _ = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
+    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
     torch.cuda.synchronize()
     ref = orc.swiglu_rows(p, tok, exp)
-    max_rel, mean_rel = err_stats(f64(act_g), ref)
+    max_rel, mean_rel = err_stats(_act_f64(act_g, sc_g), ref)
     print(f"swiglu {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e}")
-    assert max_rel <= 6e-3 and mean_rel <= 3e-3          # one bf16 rounding of an fp32 accumulation
+    if wl.fp8:
+        # re-quantised to e4m3 (3 mantissa bits) per 1x128 block with scale = amax/448
+        assert max_rel <= 2 ** -4 + 1e-3 and mean_rel <= 3.5e-2
+        q = act_g.float().abs().reshape(cfg.P, -1, 128).amax(dim=-1)
+        amax_ref = torch.from_numpy(np.abs(ref).reshape(cfg.P, -1, 128).max(axis=-1)).cuda()
+        assert ((q == 448) | (amax_ref == 0)).all(), "every non-zero block must use the full e4m3 range"
+        np.testing.assert_allclose(sc_g.cpu().numpy(), np.maximum(amax_ref.cpu().numpy(), 1e-30) / 448, rtol=1e-2)
+    else:
+        assert max_rel <= 6e-3 and mean_rel <= 3e-3      # one bf16 rounding of an fp32 accumulation
 
 
 def test_gemm_down(case):
     wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
-    act_g, _ = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
-    y_g = moe.moe_grouped_gemm_down(cfg, act_g, None, gpu.w2, gpu.w2_scale, tiles, ntiles)
+    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
+    y_g = moe.moe_grouped_gemm_down(cfg, act_g, sc_g, gpu.w2, gpu.w2_scale, tiles, ntiles)
     torch.cuda.synchronize()
-    ref = orc.down_rows(p, exp, f64(act_g))              # from the very activations the GPU consumed
+    ref = orc.down_rows(p, exp, _act_f64(act_g, sc_g))   # from the very activations the GPU consumed
     max_rel, mean_rel = err_stats(f64(y_g), ref)
     print(f"down {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e}")
     assert max_rel <= 6e-3 and mean_rel <= 3e-3
@@ -105,8 +126,10 @@ def test_combine(case):
     torch.cuda.synchronize()
     ref = orc.combine(w32.numpy().astype(np.float64), inv, f64(y))
     got = f64(out_g)
-    # fp32 sum of k exact products, one rounding to bf16: within half a bf16 ulp plus fp32 noise
-    assert (np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30).all()
+    # fp32 sum of k products, one rounding to bf16: within half a bf16 ulp of the exact sum plus
+    # the fp32 rounding of the k terms (which matters where the terms cancel)
+    mag = orc.combine(np.abs(w32.numpy()).astype(np.float64), inv, np.abs(f64(y)))
+    assert (np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + mag * 2.0 ** -21 + 1e-30).all()
     ref_bits = torch.from_numpy(ref).to(torch.bfloat16)
     assert (ref_bits.view(torch.int16) != out_g.cpu().view(torch.int16)).float().mean() < 1e-3
 
