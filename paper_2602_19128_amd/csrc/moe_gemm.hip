@@ -53,6 +53,7 @@ constexpr int GM_W_COPIES = 4;            // weight copies per wavefront per ste
 constexpr int GM_W_STAGE = 32 * 128;      // bytes of one wavefront's weight stage
 constexpr int GM_CUS = 256;
 constexpr float GM_FP8_MAX = 448.f;
+constexpr int GM_NT = 2;                 // cache policy bit "non-temporal" of a copy
 
 #define MOE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define MOE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -115,6 +116,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     const int crow = lane >> 3;                               // copy: row inside an 8-row pass
     const int cbyte = ((lane & 7) ^ crow) << 4;               // copy: byte offset of the logical chunk for this lane's slot
     const int rows = tile.rows;
+    // Weights are read once and marked non-temporal so they do not push the shared token rows out
+    // of L2.  Exception (measured): the down projection of an expert with several row tiles, whose
+    // workgroups run side by side and share each weight line through L2.
+    const bool share_weights = !SWIGLU && tile.count > 1;
     const int n_out = g.n_out;
     const size_t row_bytes = (size_t)g.K * ES;
     const int nk = (int)(row_bytes / GM_STEP_BYTES);
@@ -207,8 +212,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     {                                                                                                  \
         const int k0_ = min((s), nk - 1) * GM_STEP_BYTES;                                              \
         unsigned char *dst_ = w_ring + ((s) % SW) * GM_W_STAGE;                                        \
-        _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                        \
-            __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(w_ptr[q] + k0_), MOE_LDS_PTR(dst_ + q * 1024), 16, 0, 0); \
+        if (share_weights) {                                                                           \
+            _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                    \
+                __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(w_ptr[q] + k0_), MOE_LDS_PTR(dst_ + q * 1024), 16, 0, 0); \
+        } else {                                                                                       \
+            _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                    \
+                __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(w_ptr[q] + k0_), MOE_LDS_PTR(dst_ + q * 1024), 16, 0, GM_NT); \
+        }                                                                                              \
     }
 
     // Issue slot t (t = -DW .. nk-1) holds [token copy of step t+DA, weight copy of step t+DW].
