@@ -14,16 +14,19 @@
 //    64 lanes cover 8 rows x 128 contiguous bytes: whole cache lines per instruction.  (Loading
 //    weights straight into the MFMA register layout would touch 16 rows x 64 bytes per
 //    instruction, half lines, which measures ~20% slower on this memory system.)  Weights land
-//    in a ring private to the owning wavefront (no barrier on the weight path, DW steps ahead);
-//    the token rows (x gathered through the sorted pair list, or act) are shared by all
-//    wavefronts and land in a second ring DA steps ahead.  Physical 16-byte chunk pc of LDS row
-//    r holds logical chunk pc ^ (r & 7) (applied on the global-address side of the copy), which
-//    keeps the 16-byte MFMA fragment reads free of bank conflicts.
+//    in a ring private to the owning wavefront (no barrier on the weight path, DW steps ahead;
+//    a slot is refilled as soon as its fragments sit in registers, so the ring holds exactly the
+//    DW stages in flight); the token rows (x gathered through the sorted pair list, or act) are
+//    shared by all wavefronts and land in a second ring DA steps ahead.  Physical 16-byte chunk pc
+//    of LDS row r holds logical chunk pc ^ (r & 7) (applied on the global-address side of the
+//    copy), which keeps the 16-byte MFMA fragment reads free of bank conflicts.
 //  * One K step is 128 bytes of every row: 64 bf16 elements (two v_mfma_f32_16x16x32_bf16) or
 //    128 fp8 elements (one v_mfma_f32_16x16x128_f8f6f4, exactly one 128-wide scale block).  The
 //    weights are the row operand, so the accumulator of lane l holds 4 consecutive output
 //    columns of token l%16: the epilogue applies act = silu(g) * u in registers and stores whole
 //    8-byte (bf16) or 4-byte (fp8) pieces.
+//  * Inside a step the token fragments are software-pipelined: fragment q+PF is requested from
+//    LDS while the MFMAs of fragment q run (the order is pinned with scheduling barriers).
 //  * fp8: each K step's product is formed in a fresh accumulator and folded into the running
 //    fp32 sum with (activation scale of the token's 1x128 block) x (weight scale of the 128x128
 //    block).  Activation scales ride along with the token rows in the LDS ring; a wavefront's
@@ -34,6 +37,8 @@
 //    explicitly (s_waitcnt vmcnt(n)) so that a barrier never drains the copy queue.
 //  * Row blocks beyond the tile's real row count are skipped (the K loop is instantiated per
 //    row-block count), so an expert with 140 tokens costs 9-10 blocks of 16, not 256 rows.
+//  * Workgroups start their K loops at different columns when the row stride is a multiple of
+//    4 KiB (see k_groups_for).
 //
 // Workgroups are numbered so that each XCD (own L2) gets a contiguous range of the
 // (expert tile, column slab) work: the token rows of an expert stay in one L2.
@@ -53,11 +58,36 @@ constexpr int GM_W_COPIES = 4;            // weight copies per wavefront per ste
 constexpr int GM_W_STAGE = 32 * 128;      // bytes of one wavefront's weight stage
 constexpr int GM_CUS = 256;
 constexpr float GM_FP8_MAX = 448.f;
-constexpr int GM_NT = 2;                 // cache policy bit "non-temporal" of a copy
+constexpr int GM_NT = 2;
+constexpr int GM_PF = 4;                 // token fragments requested ahead of the MFMAs that use them (bf16)
+constexpr int GM_PF_FP8 = 2;             // the same for fp8 (a fragment is twice as large)
+                 // cache policy bit "non-temporal" of a copy
 
 #define MOE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define MOE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define MOE_WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+
+// Direct global -> LDS copies, one instruction per wavefront: lane l moves 16 (or 4) bytes from its
+// own global address to LDS byte address lds_base + 16*l (4*l).  Written as inline assembly so that
+// the compiler's wait-count bookkeeping of the ordinary LDS reads stays exact (it otherwise falls
+// back to full waits whenever such a copy is pending); the copies are tracked by hand with
+// MOE_WAIT_VMCNT.  lds_base must be wavefront-uniform.
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)(p);
+}
+template <bool NT>
+__device__ __forceinline__ void copy16_to_lds(const void *g, uint32_t lds_base)
+{
+    if constexpr (NT)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_base), "v"(g) : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory");
+}
+__device__ __forceinline__ void copy4_to_lds(const void *g, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(g) : "memory");
+}
 
 __device__ __forceinline__ int lds_off(int row, int chunk)   // byte offset of logical 16-byte chunk of a row
 {
@@ -73,6 +103,7 @@ struct GemmArgs {
     unsigned char *out;           // gate/up: act [P,n_out] (bf16 / fp8); down: y [P,n_out] bf16
     float *out_scale;             // fp8 gate/up: act_scale [P, n_out/128]
     int K, n_out, top_k;
+    int k_groups;                 // distinct K-loop starting points spread over the workgroups (1 = all start at 0)
 };
 
 // Compile-time shape of one kernel variant.
@@ -87,7 +118,7 @@ struct Shape {
     static constexpr int COLS = SLAB * NW;                    // output columns per workgroup
     static constexpr int STAGE_BYTES = MB_MAX * 16 * 128;     // one token-row stage
     static constexpr int A_RING_BYTES = (DA + 1) * STAGE_BYTES;
-    static constexpr int W_RING_BYTES = (DW + 1) * NW * GM_W_STAGE;
+    static constexpr int W_RING_BYTES = DW * NW * GM_W_STAGE;
     // one fp32 activation scale per token row, copied 64 rows (one wavefront) at a time
     static constexpr int SC_STAGE_BYTES = FP8 ? ((MB_MAX * 16 + 63) / 64) * 256 : 0;
     static constexpr int LDS_BYTES = A_RING_BYTES + W_RING_BYTES + (DA + 1) * SC_STAGE_BYTES;
@@ -98,13 +129,13 @@ struct Shape {
 
 // Everything after the (tile, column slab) decision, instantiated per active row-block count NB.
 template <class SH, int NB>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, unsigned char *smem)
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, int work, unsigned char *smem)
 {
     constexpr int NW = SH::NW, DA = SH::DA, DW = SH::DW;
     constexpr bool SWIGLU = SH::SWIGLU, FP8 = SH::FP8;
     constexpr int ES = FP8 ? 1 : 2;                           // bytes per element
     constexpr int SA = DA + 1;                                // token-row stages
-    constexpr int SW = DW + 1;                                // weight stages
+    constexpr int SW = DW;                                    // weight stages (a slot is refilled as soon as its fragments are in registers)
     constexpr int STAGE_BYTES = SH::STAGE_BYTES;
     constexpr int A_PASS_MAX = (NB * 2 + NW - 1) / NW;        // 8-row copy passes per wavefront
     constexpr int SLAB = SH::SLAB;
@@ -123,6 +154,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     const int n_out = g.n_out;
     const size_t row_bytes = (size_t)g.K * ES;
     const int nk = (int)(row_bytes / GM_STEP_BYTES);
+    // Workgroups that run side by side start their K loops at different columns (and wrap around):
+    // with every workgroup at the same column, rows whose stride is a multiple of a large power of
+    // two keep hitting the same memory channels.  The sum over K is the same set of terms.
+    const int koff = (int)((long)(work % g.k_groups) * nk / g.k_groups);
+    auto k_rot = [&](int s_) __attribute__((always_inline)) { const int r_ = s_ + koff; return r_ >= nk ? r_ - nk : r_; };
 
     // ---- weight row pointers: copy q (0..3) moves rows 8q..8q+7 of this wavefront's 32 rows
     // (rows 0..15 = first block, 16..31 = second block)
@@ -144,6 +180,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     }
     unsigned char *const w_ring = smem + SH::A_RING_BYTES + wave * (SW * GM_W_STAGE);
     unsigned char *const sc_ring = smem + SH::A_RING_BYTES + SH::W_RING_BYTES;
+    const uint32_t smem_lds = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
+    const uint32_t w_lds = __builtin_amdgcn_readfirstlane(lds_addr_of(w_ring));
+    const uint32_t sc_lds = __builtin_amdgcn_readfirstlane(lds_addr_of(sc_ring));
 
     // fp8: this wavefront's weight scales for every K step, lane l holds step l (and l + 64)
     float wsc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
@@ -196,28 +235,27 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     // number of copies per slot constant, which the explicit wait counts rely on).
 #define MOE_COPY_TOKENS(s)                                                                             \
     {                                                                                                  \
-        const int ks_ = min((s), nk - 1);                                                              \
+        const int ks_ = k_rot(min((s), nk - 1));                                                       \
         const int k0_ = ks_ * GM_STEP_BYTES;                                                           \
-        unsigned char *dst_ = smem + ((s) % SA) * STAGE_BYTES;                                         \
+        const uint32_t dst_ = smem_lds + ((s) % SA) * STAGE_BYTES;                                     \
         _Pragma("unroll") for (int i = 0; i < A_PASS_MAX; ++i)                                         \
             if (i < a_cnt - (sc_copy ? 1 : 0))                                                         \
-                __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(a_ptr[i] + k0_), MOE_LDS_PTR(dst_ + a_dst[i]), 16, 0, 0); \
+                copy16_to_lds<false>(a_ptr[i] + k0_, dst_ + a_dst[i]);                                 \
         if constexpr (FP8) {                                                                           \
             if (sc_copy)                                                                               \
-                __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(sc_ptr + ks_),                         \
-                                                 MOE_LDS_PTR(sc_ring + ((s) % SA) * SH::SC_STAGE_BYTES + wave * 256), 4, 0, 0); \
+                copy4_to_lds(sc_ptr + ks_, sc_lds + ((s) % SA) * SH::SC_STAGE_BYTES + wave * 256);     \
         }                                                                                              \
     }
 #define MOE_COPY_WEIGHTS(s)                                                                            \
     {                                                                                                  \
-        const int k0_ = min((s), nk - 1) * GM_STEP_BYTES;                                              \
-        unsigned char *dst_ = w_ring + ((s) % SW) * GM_W_STAGE;                                        \
+        const int k0_ = k_rot(min((s), nk - 1)) * GM_STEP_BYTES;                                       \
+        const uint32_t dst_ = w_lds + ((s) % SW) * GM_W_STAGE;                                         \
         if (share_weights) {                                                                           \
             _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                    \
-                __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(w_ptr[q] + k0_), MOE_LDS_PTR(dst_ + q * 1024), 16, 0, 0); \
+                copy16_to_lds<false>(w_ptr[q] + k0_, dst_ + q * 1024);                                 \
         } else {                                                                                       \
             _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                    \
-                __builtin_amdgcn_global_load_lds(MOE_GLOBAL_PTR(w_ptr[q] + k0_), MOE_LDS_PTR(dst_ + q * 1024), 16, 0, GM_NT); \
+                copy16_to_lds<true>(w_ptr[q] + k0_, dst_ + q * 1024);                                  \
         }                                                                                              \
     }
 
@@ -250,18 +288,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 #undef MOE_WAIT_FOR_STEP
         asm volatile("s_barrier" ::: "memory");               // token stage s complete for everyone; stage s-1 free
         MOE_COPY_TOKENS(s + DA)
-        MOE_COPY_WEIGHTS(s + DW)
         __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sa = smem + (s % SA) * STAGE_BYTES;
         const unsigned char *sw = w_ring + (s % SW) * GM_W_STAGE;
         if constexpr (FP8) {
             // one MFMA spans the whole step: lane (l16, lq) holds bytes 32*lq .. 32*lq+31 of its row
             const float *ssc = reinterpret_cast<const float *>(sc_ring + (s % SA) * SH::SC_STAGE_BYTES);
-            const int sl = s & 63;
+            const int sr = k_rot(s);
+            const int sl = sr & 63;
             const float sw0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(
-                __builtin_bit_cast(int, s < 64 ? wsc[0][0] : wsc[0][1]), sl));
+                __builtin_bit_cast(int, sr < 64 ? wsc[0][0] : wsc[0][1]), sl));
             const float sw1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(
-                __builtin_bit_cast(int, s < 64 ? wsc[1][0] : wsc[1][1]), sl));
+                __builtin_bit_cast(int, sr < 64 ? wsc[1][0] : wsc[1][1]), sl));
+            constexpr int PF = NB < GM_PF_FP8 ? NB : GM_PF_FP8;
             i32x8 w0, w1;
             {
                 const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(sw + lds_off(l16, 2 * lq));
@@ -271,35 +310,81 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
                 w0 = i32x8{(int)lo0.x, (int)lo0.y, (int)lo0.z, (int)lo0.w, (int)hi0.x, (int)hi0.y, (int)hi0.z, (int)hi0.w};
                 w1 = i32x8{(int)lo1.x, (int)lo1.y, (int)lo1.z, (int)lo1.w, (int)hi1.x, (int)hi1.y, (int)hi1.z, (int)hi1.w};
             }
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4 tlo[PF], thi[PF];
+            float tsx[PF];
+#define MOE_LOAD_TOK8(slot, m_)                                                                        \
+            {                                                                                          \
+                tlo[slot] = *reinterpret_cast<const u32x4 *>(sa + lds_off((m_) * 16 + l16, 2 * lq));     \
+                thi[slot] = *reinterpret_cast<const u32x4 *>(sa + lds_off((m_) * 16 + l16, 2 * lq + 1)); \
+                tsx[slot] = ssc[(m_) * 16 + l16];                                                      \
+            }
 #pragma unroll
-            for (int m = 0; m < NB; ++m) {
-                const u32x4 lo = *reinterpret_cast<const u32x4 *>(sa + lds_off(m * 16 + l16, 2 * lq));
-                const u32x4 hi = *reinterpret_cast<const u32x4 *>(sa + lds_off(m * 16 + l16, 2 * lq + 1));
-                const i32x8 t = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-                const float sx = ssc[m * 16 + l16];
-                const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
-                // e4m3 x e4m3, hardware block scales set to 1.0 (E8M0 0x7f): the fp32 scales are applied below
-                const f32x4 p0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w0, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-                const f32x4 p1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w1, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-                const float f0 = sx * sw0, f1 = sx * sw1;
+            for (int q = 0; q < PF; ++q) MOE_LOAD_TOK8(q, q)
+            __builtin_amdgcn_sched_barrier(0);
+            f32x4 p0[2], p1[2];
+            float fs0[2], fs1[2];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    acc[m][0][v] = fmaf(p0[v], f0, acc[m][0][v]);
-                    acc[m][1][v] = fmaf(p1[v], f1, acc[m][1][v]);
+            for (int m = 0; m <= NB; ++m) {
+                if (m < NB) {
+                    const u32x4 lo = tlo[m % PF], hi = thi[m % PF];
+                    const i32x8 t = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+                    const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+                    // e4m3 x e4m3, hardware block scales set to 1.0 (E8M0 0x7f): the fp32 scales are applied below
+                    p0[m & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w0, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                    p1[m & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w1, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                    fs0[m & 1] = tsx[m % PF] * sw0;
+                    fs1[m & 1] = tsx[m % PF] * sw1;
+                    if (m + PF < NB) MOE_LOAD_TOK8(m % PF, m + PF)
+                }
+                if (m > 0) {
+                    const int pm = m - 1;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        acc[pm][0][v] = fmaf(p0[pm & 1][v], fs0[pm & 1], acc[pm][0][v]);
+                        acc[pm][1][v] = fmaf(p1[pm & 1][v], fs1[pm & 1], acc[pm][1][v]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (m == 0) {
+                    // the MFMAs above waited for the weight fragments (LDS reads return in order and the
+                    // token fragment was requested after them): the weight slot may be refilled
+                    MOE_COPY_WEIGHTS(s + DW)
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
+#undef MOE_LOAD_TOK8
         } else {
+            // Software pipeline over the 2*NB token fragments of this step: fragment q+PF is read
+            // from LDS while the MFMAs of fragment q run.
+            constexpr int NQ = 2 * NB;
+            constexpr int PF = NQ < GM_PF ? NQ : GM_PF;
+            bf16x8 wf[2][2], tf[PF];
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 w0 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(l16, kk * 4 + lq));
-                const bf16x8 w1 = *reinterpret_cast<const bf16x8 *>(sw + lds_off(16 + l16, kk * 4 + lq));
+                wf[kk][0] = *reinterpret_cast<const bf16x8 *>(sw + lds_off(l16, kk * 4 + lq));
+                wf[kk][1] = *reinterpret_cast<const bf16x8 *>(sw + lds_off(16 + l16, kk * 4 + lq));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#define MOE_LOAD_TOK(q_) (*reinterpret_cast<const bf16x8 *>(sa + lds_off(((q_) % NB) * 16 + l16, ((q_) / NB) * 4 + lq)))
 #pragma unroll
-                for (int m = 0; m < NB; ++m) {
-                    const bf16x8 t = *reinterpret_cast<const bf16x8 *>(sa + lds_off(m * 16 + l16, kk * 4 + lq));
-                    acc[m][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, t, acc[m][0], 0, 0, 0);
-                    acc[m][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, t, acc[m][1], 0, 0, 0);
+            for (int q = 0; q < PF; ++q) tf[q] = MOE_LOAD_TOK(q);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int kk = q / NB, m = q % NB;
+                acc[m][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[kk][0], tf[q % PF], acc[m][0], 0, 0, 0);
+                acc[m][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[kk][1], tf[q % PF], acc[m][1], 0, 0, 0);
+                if (q + PF < NQ) tf[q % PF] = MOE_LOAD_TOK(q + PF);
+                __builtin_amdgcn_sched_barrier(0);
+                if (q == 0) {
+                    // the MFMAs above waited for all four weight fragments (LDS reads return in order and
+                    // the token fragment was requested after them): the weight slot may be refilled
+                    MOE_COPY_WEIGHTS(s + DW)
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
+#undef MOE_LOAD_TOK
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -384,7 +469,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 }
 
 template <class SH, int NB>
-__device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const moe_tile &tile, int ct,
+__device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const moe_tile &tile, int ct, int work,
                                                 unsigned char *smem)
 {
     if constexpr (NB > SH::MB_MAX) {
@@ -392,8 +477,8 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
     } else {
         // row-block counts are rounded up to even above 4 to bound the number of instantiations
         constexpr int NEXT = NB < 4 ? NB + 1 : NB + 2;
-        if (nb <= NB) gemm_tile<SH, NB>(g, tile, ct, smem);
-        else dispatch_blocks<SH, NEXT>(nb, g, tile, ct, smem);
+        if (nb <= NB) gemm_tile<SH, NB>(g, tile, ct, work, smem);
+        else dispatch_blocks<SH, NEXT>(nb, g, tile, ct, work, smem);
     }
 }
 
@@ -413,7 +498,7 @@ __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, c
     const int ct = local / head.count;                         // column slab
     const moe_tile tile = tiles[head.first + local % head.count];
     const int nb = ceil_div(tile.rows, 16);
-    dispatch_blocks<SH, 1>(nb, g, tile, ct, smem);
+    dispatch_blocks<SH, 1>(nb, g, tile, ct, work, smem);
 }
 
 template <class SH>
@@ -440,7 +525,7 @@ int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *nti
                     hipStream_t s)
 {
     constexpr int DA = MB_MAX >= 16 ? 1 : 2;                  // 16 row blocks: 32 KiB per token stage
-    constexpr int DW = (MB_MAX >= 16 && FP8) ? 1 : 2;         // the scale ring of the largest fp8 tile needs the room
+    constexpr int DW = 2;
     using Wide = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8>;
     if constexpr (!(FP8 && SWIGLU)) {
         using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU, FP8>;
@@ -472,6 +557,15 @@ int expected_tiles(const moe_config &c)
     return (int)(pairs < c.E ? pairs : c.E);
 }
 
+// Number of distinct K-loop starting points for rows of `row_bytes` bytes: every K step its own
+// when the row stride is a multiple of 4 KiB (measured: such strides lose 10-15% of the stream rate
+// when all workgroups walk K in step; other strides gain nothing and only spread the token rows
+// over more of L2).
+int k_groups_for(int row_bytes)
+{
+    return row_bytes % 4096 == 0 ? row_bytes / GM_STEP_BYTES : 1;
+}
+
 }  // namespace
 
 int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const void *x,
@@ -479,7 +573,8 @@ int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const 
                        const moe_tile *tiles, const int32_t *ntiles, void *act, float *act_scale, hipStream_t s)
 {
     GemmArgs g{static_cast<const unsigned char *>(x), x_scale, static_cast<const unsigned char *>(w1), w1_scale,
-               sorted_pair, static_cast<unsigned char *>(act), act_scale, c.H, c.I, c.top_k};
+               sorted_pair, static_cast<unsigned char *>(act), act_scale, c.H, c.I, c.top_k,
+               k_groups_for(c.H * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2))};
     if (c.dtype == MOE_DTYPE_FP8_E4M3) {
         if (c.H > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;  // weight scales of one slab sit in two registers
         return launch_by_tile_rows<true, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
@@ -492,7 +587,8 @@ int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const vo
                      hipStream_t s)
 {
     GemmArgs g{static_cast<const unsigned char *>(act), act_scale, static_cast<const unsigned char *>(w2), w2_scale,
-               nullptr, static_cast<unsigned char *>(y), nullptr, c.I, c.H, c.top_k};
+               nullptr, static_cast<unsigned char *>(y), nullptr, c.I, c.H, c.top_k,
+               k_groups_for(c.I * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2))};
     if (c.dtype == MOE_DTYPE_FP8_E4M3) {
         if (c.I > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;
         return launch_by_tile_rows<false, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
