@@ -58,13 +58,10 @@ constexpr int GM_W_COPIES = 4;            // weight copies per wavefront per ste
 constexpr int GM_W_STAGE = 32 * 128;      // bytes of one wavefront's weight stage
 constexpr int GM_CUS = 256;
 constexpr float GM_FP8_MAX = 448.f;
-constexpr int GM_NT = 2;
 constexpr int GM_PF = 4;                 // token fragments requested ahead of the MFMAs that use them (bf16)
 constexpr int GM_PF_FP8 = 2;             // the same for fp8 (a fragment is twice as large)
                  // cache policy bit "non-temporal" of a copy
 
-#define MOE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
-#define MOE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define MOE_WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 
 // Direct global -> LDS copies, one instruction per wavefront: lane l moves 16 (or 4) bytes from its

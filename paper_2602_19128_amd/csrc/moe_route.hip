@@ -1,6 +1,7 @@
 // Routing (paper Sec. 4.5 "Routing"): score every expert for every token, keep the top-k.
 //
-// Two kernels:
+// Few experts (<= 16): router_few_experts_kernel does everything for a token in one wavefront.
+// Otherwise two kernels:
 //   router_logits_kernel  z = x . router_w^T in fp32, LDS-tiled, split along H so that a
 //                         handful of decode tokens still fills the chip; partial sums go
 //                         to scratch and are added in a fixed order (deterministic).
@@ -189,29 +190,16 @@ struct TopkParams {
     float routed_scale;
 };
 
-// Lane l owns experts l*EPL .. l*EPL+EPL-1 (contiguous, so a group of experts is a run of lanes).
+// Scoring rule, optional group limiting and top-k of one token by one wavefront.  Lane l owns
+// experts l*EPL .. l*EPL+EPL-1 (contiguous, so a group of experts is a run of lanes); z holds
+// their logits.
 template <int EPL>
-__global__ __launch_bounds__(256) void router_topk_kernel(const float *__restrict__ zpart,
-                                                          const float *__restrict__ bias,
-                                                          int32_t *__restrict__ ids, float *__restrict__ w,
-                                                          TopkParams p)
+__device__ __forceinline__ void route_token(const float (&z)[EPL], int lane, int t, const float *__restrict__ bias,
+                                            int32_t *__restrict__ ids, float *__restrict__ w, const TopkParams &p)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int t = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (t >= p.T) return;                                  // whole wave leaves together
     const int E = p.E;
-
-    float z[EPL], s[EPL];
+    float s[EPL];
     unsigned long long key[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-        const int e = lane * EPL + i;
-        float acc = 0.f;
-        if (e < E)
-            for (int sp = 0; sp < p.splits; ++sp) acc += zpart[((size_t)sp * p.T + t) * E + e];
-        z[i] = acc;
-    }
-
     if (p.scoring == MOE_SCORE_SOFTMAX) {
         float m = -INFINITY;
 #pragma unroll
@@ -296,6 +284,102 @@ __global__ __launch_bounds__(256) void router_topk_kernel(const float *__restric
     }
 }
 
+// One wavefront per token: adds the partial logits of the H splits, then routes the token.
+template <int EPL>
+__global__ __launch_bounds__(256) void router_topk_kernel(const float *__restrict__ zpart,
+                                                          const float *__restrict__ bias,
+                                                          int32_t *__restrict__ ids, float *__restrict__ w,
+                                                          TopkParams p)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int t = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (t >= p.T) return;                                  // whole wave leaves together
+    const int E = p.E;
+    float z[EPL];
+    // partial logits of the H splits, added in split order; the loads of eight splits are issued
+    // together so that their latencies overlap
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) z[i] = 0.f;
+    for (int sp0 = 0; sp0 < p.splits; sp0 += 8) {
+        float part[8][EPL];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) {
+                const int e = lane * EPL + i;
+                part[u][i] = (e < E && sp0 + u < p.splits) ? zpart[((size_t)(sp0 + u) * p.T + t) * E + e] : 0.f;
+            }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) z[i] += part[u][i];
+    }
+
+    route_token<EPL>(z, lane, t, bias, ids, w, p);
+}
+
+// Few experts (E <= RT_FEW): logits and routing of a token in one wavefront, one launch.  The
+// lanes split H (8 consecutive elements per lane and pass); every lane keeps one running sum per
+// expert, a butterfly adds them across the wavefront in a fixed order.
+constexpr int RT_FEW = 16;
+
+template <bool FP8>
+__global__ __launch_bounds__(256) void router_few_experts_kernel(const void *__restrict__ x,
+                                                                 const float *__restrict__ x_scale,
+                                                                 const float *__restrict__ router_w,
+                                                                 const float *__restrict__ bias,
+                                                                 int32_t *__restrict__ ids, float *__restrict__ w,
+                                                                 TopkParams p, int H)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int t = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (t >= p.T) return;                                  // whole wave leaves together
+    const int E = p.E;
+    float acc[RT_FEW];
+#pragma unroll
+    for (int e = 0; e < RT_FEW; ++e) acc[e] = 0.f;
+    // four passes per iteration so that the loads of all of them are in flight together
+    for (int h0 = lane * 8; h0 < H; h0 += 4 * kWave * 8) {
+        float xv[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) load_x8<FP8>(x, x_scale, p.T, H, t, h0 + u * kWave * 8, xv[u]);
+#pragma unroll
+        for (int e = 0; e < RT_FEW; ++e) {
+            if (e < E) {
+                float4 a[4], b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int h = h0 + u * kWave * 8;
+                    if (h < H) {
+                        const float4 *src = reinterpret_cast<const float4 *>(router_w + (size_t)e * H + h);
+                        a[u] = src[0]; b[u] = src[1];
+                    } else {
+                        a[u] = b[u] = float4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float part = xv[u][0] * a[u].x;        // short chain per pass, added to the running sum
+                    part = fmaf(xv[u][1], a[u].y, part); part = fmaf(xv[u][2], a[u].z, part);
+                    part = fmaf(xv[u][3], a[u].w, part); part = fmaf(xv[u][4], b[u].x, part);
+                    part = fmaf(xv[u][5], b[u].y, part); part = fmaf(xv[u][6], b[u].z, part);
+                    part = fmaf(xv[u][7], b[u].w, part);
+                    acc[e] += part;
+                }
+            }
+        }
+    }
+    float z[1] = {0.f};
+#pragma unroll
+    for (int e = 0; e < RT_FEW; ++e) {
+        if (e < E) {
+            const float total = wave_sum_f32(acc[e]);
+            if (lane == e) z[0] = total;
+        }
+    }
+    route_token<1>(z, lane, t, bias, ids, w, p);
+}
+
 }  // namespace
 
 size_t route_workspace_bytes(const moe_config &c)
@@ -307,6 +391,18 @@ size_t route_workspace_bytes(const moe_config &c)
 int launch_route(const moe_config &c, const void *x, const float *x_scale, const float *router_w,
                  const float *bias, int32_t *ids, float *w, void *ws, hipStream_t s)
 {
+    TopkParams p{c.T, c.E, c.top_k, c.scoring, c.renormalize, c.n_group, c.topk_group,
+                 c.group_score_topn, 1, c.routed_scale};
+    if (c.E <= RT_FEW) {
+        const dim3 fgrid(ceil_div(c.T, 4));
+        if (c.dtype == MOE_DTYPE_FP8_E4M3)
+            hipLaunchKernelGGL(router_few_experts_kernel<true>, fgrid, dim3(256), 0, s, x, x_scale, router_w, bias,
+                               ids, w, p, c.H);
+        else
+            hipLaunchKernelGGL(router_few_experts_kernel<false>, fgrid, dim3(256), 0, s, x, x_scale, router_w, bias,
+                               ids, w, p, c.H);
+        return check_launch();
+    }
     const RouteGrid g = route_grid(c);
     float *zpart = static_cast<float *>(ws);
     const dim3 grid(g.tiles_t, g.tiles_e, g.splits);
@@ -319,8 +415,7 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
     int rc = check_launch();
     if (rc != MOE_OK) return rc;
 
-    TopkParams p{c.T, c.E, c.top_k, c.scoring, c.renormalize, c.n_group, c.topk_group,
-                 c.group_score_topn, g.splits, c.routed_scale};
+    p.splits = g.splits;
     const dim3 tgrid(ceil_div(c.T, 4));
     const int epl = c.E <= 64 ? 1 : c.E <= 128 ? 2 : c.E <= 256 ? 4 : 8;
     switch (epl) {
