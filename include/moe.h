@@ -25,6 +25,13 @@
  *     lanes per group (see moe_route) and top_k <= topk_group * E / n_group.
  *   - Notation: T tokens, H hidden size, I expert intermediate size, E experts,
  *     k = top_k, P = T*k (token, slot) pairs, pair id p = t*k + j.
+ *   - Local-expert mode (the share of the layer one device holds under expert
+ *     parallelism; the paper's Sec. 4.5 workload is 32 local experts of 256):
+ *     the router still scores all E experts, but only experts
+ *     [local_expert_offset, local_expert_offset + num_local_experts) have weights
+ *     here.  Pairs routed elsewhere are dropped by the sort-scatter and contribute
+ *     nothing to `out`, which is then this device's partial sum of the layer.
+ *     EL below is num_local_experts, or E when that field is 0.
  */
 #ifndef MOE_H
 #define MOE_H
@@ -61,6 +68,8 @@ typedef struct moe_config {
     int32_t group_score_topn;
     int32_t dtype;              /* payload type of x, w1, w2 (and of the act buffer) */
     float   routed_scale;       /* final factor on the k weights */
+    int32_t local_expert_offset;/* first expert whose weights this call holds */
+    int32_t num_local_experts;  /* how many it holds; 0 = all E (then the offset must be 0) */
 } moe_config;
 
 /* Row count of one tile of the grouped GEMMs for this problem (the height the
@@ -98,13 +107,15 @@ int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const 
 /*
  * Sort-scatter (paper Sec. 4.5: reorder tokens by expert into contiguous memory).
  * A stable counting sort of the P pairs by expert id:
- *   ids          [P] int32 (= the [T,k] routing result); ids outside [0,E) drop the pair
- *   offsets_out  [E+1] int32, first sorted row of each expert; offsets[E] = kept pairs
+ *   ids          [P] int32 (= the [T,k] routing result); an id outside the local expert
+ *                range drops the pair
+ *   offsets_out  [EL+1] int32, first sorted row of each local expert; offsets[EL] = kept pairs
  *   sorted_pair_out [P] int32, pair stored at each sorted row (ascending p inside an expert)
  *   inv_out      [P] int32, sorted row of each pair (-1 for a dropped pair)
  *   tiles_out    [moe_max_tiles(cfg)] records cut at moe_tile_rows(cfg) rows, experts in
  *                ascending order, none for an expert without tokens (such experts cost
- *                nothing downstream); ntiles_out [1] int32 = records written
+ *                nothing downstream); `expert` counts from the first local expert (it
+ *                indexes w1 / w2); ntiles_out [1] int32 = records written
  */
 int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
                 int32_t *sorted_pair_out, int32_t *inv_out, moe_tile *tiles_out,
@@ -115,9 +126,9 @@ int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
  * projection combined via SiLU, on matrix cores with double-buffered tiles).
  * For sorted row r of expert e holding pair p (token t = p / k):
  *   g = x[t,:] . w1[e,i,:],  u = x[t,:] . w1[e,I+i,:],  act[r,i] = g*sigmoid(g)*u
- *   w1 [E,2I,H] (rows [0,I) gate, [I,2I) up), fp32 accumulation.
+ *   w1 [EL,2I,H] (rows [0,I) gate, [I,2I) up), fp32 accumulation.
  *   bf16: act_out [P,I] bf16, scales NULL.
- *   fp8 : w1_scale [E,2I/128,H/128], x_scale [T,H/128]; act_out [P,I] fp8 e4m3 and
+ *   fp8 : w1_scale [EL,2I/128,H/128], x_scale [T,H/128]; act_out [P,I] fp8 e4m3 and
  *         act_scale_out [P,I/128] fp32 (act re-quantised per 1x128 block, scale = amax/448).
  */
 int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x_scale,
@@ -127,8 +138,8 @@ int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x
 
 /*
  * Down grouped GEMM (paper Sec. 4.5: "then a down-projection"):
- *   y[r,h] = act[r,:] . w2[e,h,:],  w2 [E,H,I], fp32 accumulation, y_out [P,H] bf16.
- *   fp8: act_scale [P,I/128], w2_scale [E,H/128,I/128]; else NULL.
+ *   y[r,h] = act[r,:] . w2[e,h,:],  w2 [EL,H,I], fp32 accumulation, y_out [P,H] bf16.
+ *   fp8: act_scale [P,I/128], w2_scale [EL,H/128,I/128]; else NULL.
  */
 int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *act_scale,
                           const void *w2, const float *w2_scale, const moe_tile *tiles,

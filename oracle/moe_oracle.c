@@ -49,6 +49,12 @@ typedef struct {
     const float *w1_scale;      /* [E,2I/128,H/128]     (fp8 only) */
     const void  *w2;            /* [E,H,I] */
     const float *w2_scale;      /* [E,H/128,I/128]      (fp8 only) */
+    /* Local-expert mode (one device's share of the experts; the paper's Sec. 4.5 workload has
+     * 32 local experts of 256): only experts [local_offset, local_offset + local_count) have
+     * weights -- w1, w2 and their scales then hold local_count experts, indexed from
+     * local_offset -- and the layer output is the sum over a token's chosen experts that
+     * fall in that range.  local_count = 0: every expert is local. */
+    int32_t local_offset, local_count;
 } oracle_problem;
 
 /* ---- element decoding ---------------------------------------------------- */
@@ -251,6 +257,7 @@ void oracle_permute(int32_t P, int32_t E, const int32_t *ids,
  *   g[i] = sum_h x[t,h] * W1[e,i,h]        (rows [0,I)  of W1[e] = gate)
  *   u[i] = sum_h x[t,h] * W1[e,I+i,h]      (rows [I,2I) of W1[e] = up)
  *   act[r,i] = g * sigmoid(g) * u
+ * expert[r] indexes the weight arrays (in local-expert mode: counted from the first local expert).
  */
 void oracle_swiglu_rows(const oracle_problem *q, int32_t n, const int32_t *tok, const int32_t *expert,
                         double *act /* [n,I] */)
@@ -287,7 +294,8 @@ void oracle_down_rows(const oracle_problem *q, int32_t n, const int32_t *expert,
 }
 
 /* Weighted sum over each token's k expert rows, in slot order j = 0..k-1:
- *   out[t,h] = sum_j w[t,j] * y[inv[t*k+j], h]. */
+ *   out[t,h] = sum_j w[t,j] * y[inv[t*k+j], h].
+ * A pair without a row (inv < 0: its expert is not held here) contributes nothing. */
 void oracle_combine(int32_t T, int32_t k, int32_t H, const double *w /* [T,k] */,
                     const int32_t *inv /* [T*k] */, const double *y /* [T*k,H] */, double *out /* [T,H] */)
 {
@@ -295,8 +303,10 @@ void oracle_combine(int32_t T, int32_t k, int32_t H, const double *w /* [T,k] */
     for (int t = 0; t < T; ++t)
         for (int h = 0; h < H; ++h) {
             double acc = 0.0;
-            for (int j = 0; j < k; ++j)
-                acc += w[(size_t)t * k + j] * y[(size_t)inv[(size_t)t * k + j] * H + h];
+            for (int j = 0; j < k; ++j) {
+                const int32_t row = inv[(size_t)t * k + j];
+                if (row >= 0) acc += w[(size_t)t * k + j] * y[(size_t)row * H + h];
+            }
             out[(size_t)t * H + h] = acc;
         }
 }
@@ -305,6 +315,8 @@ void oracle_combine(int32_t T, int32_t k, int32_t H, const double *w /* [T,k] */
  * The whole layer for a list of tokens, straight from the definition (no
  * reordering by expert is needed to define the result):
  *   out[t,:] = sum_j w[t,j] * Down_{e_j}( SiLU(Gate_{e_j} x_t) * Up_{e_j} x_t )
+ * In local-expert mode the sum runs over the chosen experts that are local (the routing
+ * itself, and the weights w, are those of the full layer).
  * Also returns the routing it used (ids, w, margin) for those tokens.
  */
 void oracle_forward_tokens(const oracle_problem *q, int32_t n, const int32_t *tokens,
@@ -324,6 +336,10 @@ void oracle_forward_tokens(const oracle_problem *q, int32_t n, const int32_t *to
         for (int j = 0; j < k; ++j) {
             tok1 = t;
             exp1 = ids[(size_t)r * k + j];
+            if (q->local_count > 0) {
+                if (exp1 < q->local_offset || exp1 >= q->local_offset + q->local_count) continue;
+                exp1 -= q->local_offset;               /* index into the local weight arrays */
+            }
             oracle_swiglu_rows(q, 1, &tok1, &exp1, act);
             oracle_down_rows(q, 1, &exp1, act, y);
             for (int h = 0; h < H; ++h) out[(size_t)r * H + h] += w[(size_t)r * k + j] * y[h];

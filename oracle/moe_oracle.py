@@ -36,6 +36,7 @@ class _Problem(C.Structure):
         ("routed_scale", C.c_float),
         ("x", C.c_void_p), ("x_scale", C.c_void_p), ("router_w", C.c_void_p), ("bias", C.c_void_p),
         ("w1", C.c_void_p), ("w1_scale", C.c_void_p), ("w2", C.c_void_p), ("w2_scale", C.c_void_p),
+        ("local_offset", C.c_int32), ("local_count", C.c_int32),
     ]
 
 
@@ -100,6 +101,12 @@ class Problem:
     w1_scale: Optional[object] = None
     w2: Optional[object] = None
     w2_scale: Optional[object] = None
+    local_offset: int = 0             # local-expert mode: weights hold experts [offset, offset+count)
+    local_count: int = 0              # 0 = all E experts
+
+    @property
+    def EL(self) -> int:
+        return self.local_count if self.local_count > 0 else self.E
 
     def __post_init__(self):
         pay = np.uint8 if self.fp8 else np.uint16
@@ -116,9 +123,10 @@ class Problem:
         if self._rw is not None:
             assert self._rw.size == self.E * self.H
         if self._w1 is not None:
-            assert self._w1.size == self.E * 2 * self.I * self.H
+            assert self._w1.size == self.EL * 2 * self.I * self.H
         if self._w2 is not None:
-            assert self._w2.size == self.E * self.H * self.I
+            assert self._w2.size == self.EL * self.H * self.I
+        assert 0 <= self.local_offset and self.local_offset + self.local_count <= self.E
         if self.fp8:
             assert self.H % 128 == 0 and self.I % 128 == 0
         self._c = _Problem(
@@ -126,7 +134,8 @@ class Problem:
             {"softmax": 0, "sigmoid": 1}[self.scoring], int(self.renormalize), self.n_group,
             self.topk_group, self.group_score_topn, int(self.fp8), float(self.routed_scale),
             _ptr(self._x), _ptr(self._xs), _ptr(self._rw), _ptr(self._b),
-            _ptr(self._w1), _ptr(self._w1s), _ptr(self._w2), _ptr(self._w2s))
+            _ptr(self._w1), _ptr(self._w1s), _ptr(self._w2), _ptr(self._w2s),
+            self.local_offset, self.local_count)
 
 
 def problem_from_inputs(inp) -> Problem:
@@ -136,7 +145,8 @@ def problem_from_inputs(inp) -> Problem:
                    renormalize=True, n_group=wl.n_group, topk_group=wl.topk_group,
                    group_score_topn=wl.group_score_topn, routed_scale=wl.routed_scale, fp8=wl.fp8,
                    x=inp.x, x_scale=inp.x_scale, router_w=inp.router_w, bias=inp.bias,
-                   w1=inp.w1, w1_scale=inp.w1_scale, w2=inp.w2, w2_scale=inp.w2_scale)
+                   w1=inp.w1, w1_scale=inp.w1_scale, w2=inp.w2, w2_scale=inp.w2_scale,
+                   local_offset=getattr(wl, "local_offset", 0), local_count=getattr(wl, "local_experts", 0))
 
 
 def _i32(a):

@@ -35,17 +35,23 @@ class MoEConfig(C.Structure):
         ("scoring", C.c_int32), ("renormalize", C.c_int32), ("n_group", C.c_int32),
         ("topk_group", C.c_int32), ("group_score_topn", C.c_int32), ("dtype", C.c_int32),
         ("routed_scale", C.c_float),
+        ("local_expert_offset", C.c_int32), ("num_local_experts", C.c_int32),
     ]
 
     @classmethod
     def from_workload(cls, wl) -> "MoEConfig":
         return cls(wl.T, wl.H, wl.I, wl.E, wl.top_k, {"softmax": 0, "sigmoid": 1}[wl.scoring], 1,
                    wl.n_group, wl.topk_group, wl.group_score_topn, 1 if wl.fp8 else 0,
-                   float(wl.routed_scale))
+                   float(wl.routed_scale), wl.local_offset, wl.local_experts)
 
     @property
     def P(self) -> int:
         return self.T * self.top_k
+
+    @property
+    def EL(self) -> int:
+        """Experts whose weights the call holds (all E unless local-expert mode is on)."""
+        return self.num_local_experts if self.num_local_experts > 0 else self.E
 
 
 _lib = None
@@ -164,7 +170,7 @@ def moe_permute(cfg, ids):
     dev = ids.device
     _expect(ids, (cfg.T, cfg.top_k), torch.int32, "ids")
     P = cfg.P
-    offsets = torch.empty((cfg.E + 1,), dtype=torch.int32, device=dev)
+    offsets = torch.empty((cfg.EL + 1,), dtype=torch.int32, device=dev)
     sorted_pair = torch.empty((max(P, 1),), dtype=torch.int32, device=dev)
     inv = torch.empty((max(P, 1),), dtype=torch.int32, device=dev)
     tiles = torch.zeros((max(moe_max_tiles(cfg), 1), TILE_INTS), dtype=torch.int32, device=dev)
@@ -178,7 +184,7 @@ def moe_permute(cfg, ids):
 def moe_grouped_gemm_swiglu(cfg, x, x_scale, w1, w1_scale, sorted_pair, tiles, ntiles):
     dev = x.device
     _expect(x, (cfg.T, cfg.H), _payload(cfg), "x")
-    _expect(w1, (cfg.E, 2 * cfg.I, cfg.H), _payload(cfg), "w1")
+    _expect(w1, (cfg.EL, 2 * cfg.I, cfg.H), _payload(cfg), "w1")
     act = torch.empty((cfg.P, cfg.I), dtype=_payload(cfg), device=dev)
     act_scale = torch.empty((cfg.P, cfg.I // 128), dtype=torch.float32, device=dev) if cfg.dtype == 1 else None
     rc = load().moe_grouped_gemm_swiglu(C.byref(cfg), _p(x), _p(x_scale), _p(w1), _p(w1_scale), _p(sorted_pair),
@@ -190,7 +196,7 @@ def moe_grouped_gemm_swiglu(cfg, x, x_scale, w1, w1_scale, sorted_pair, tiles, n
 def moe_grouped_gemm_down(cfg, act, act_scale, w2, w2_scale, tiles, ntiles):
     dev = act.device
     _expect(act, (cfg.P, cfg.I), _payload(cfg), "act")
-    _expect(w2, (cfg.E, cfg.H, cfg.I), _payload(cfg), "w2")
+    _expect(w2, (cfg.EL, cfg.H, cfg.I), _payload(cfg), "w2")
     y = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device=dev)
     rc = load().moe_grouped_gemm_down(C.byref(cfg), _p(act), _p(act_scale), _p(w2), _p(w2_scale), _p(tiles),
                                       _p(ntiles), _p(y), _stream())
@@ -217,8 +223,8 @@ def moe_forward(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out
     dev = x.device
     _expect(x, (cfg.T, cfg.H), _payload(cfg), "x")
     _expect(router_w, (cfg.E, cfg.H), torch.float32, "router_w")
-    _expect(w1, (cfg.E, 2 * cfg.I, cfg.H), _payload(cfg), "w1")
-    _expect(w2, (cfg.E, cfg.H, cfg.I), _payload(cfg), "w2")
+    _expect(w1, (cfg.EL, 2 * cfg.I, cfg.H), _payload(cfg), "w1")
+    _expect(w2, (cfg.EL, cfg.H, cfg.I), _payload(cfg), "w2")
     out = torch.empty((cfg.T, cfg.H), dtype=torch.bfloat16, device=dev) if out is None else out
     workspace = _bytes(moe_workspace_size(cfg), dev) if workspace is None else workspace
     args = (C.byref(cfg), _p(x), _p(x_scale), _p(router_w), _p(bias), _p(w1), _p(w1_scale), _p(w2),

@@ -24,6 +24,9 @@ int validate(const moe_config *c)
     if (c->H % 64 != 0 || c->I % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if (c->dtype == MOE_DTYPE_FP8_E4M3 && (c->H % kQBlock != 0 || c->I % kQBlock != 0)) return MOE_ERR_UNSUPPORTED;
     if ((long long)c->T * c->top_k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
+    if (c->local_expert_offset < 0 || c->num_local_experts < 0) return MOE_ERR_INVALID;
+    if (c->num_local_experts == 0 && c->local_expert_offset != 0) return MOE_ERR_INVALID;
+    if (c->local_expert_offset + c->num_local_experts > c->E) return MOE_ERR_INVALID;
     if (c->n_group > 1) {
         if (c->E % c->n_group != 0) return MOE_ERR_INVALID;
         const int gsz = c->E / c->n_group;
@@ -51,7 +54,8 @@ int tile_rows_for(const moe_config &c)
 int max_tiles_for(const moe_config &c)
 {
     const int P = c.T * c.top_k;
-    return ceil_div(P, tile_rows_for(c)) + (P < c.E ? P : c.E);
+    const int el = local_experts(c);
+    return ceil_div(P, tile_rows_for(c)) + (P < el ? P : el);
 }
 
 // Workspace sections of moe_forward, in order, each 256-byte aligned.
@@ -69,7 +73,7 @@ Layout layout_for(const moe_config &c)
     l.route = take(route_workspace_bytes(c));
     l.ids = take(P * sizeof(int32_t));
     l.w = take(P * sizeof(float));
-    l.offsets = take(((size_t)c.E + 1) * sizeof(int32_t));
+    l.offsets = take(((size_t)local_experts(c) + 1) * sizeof(int32_t));
     l.sorted_pair = take(P * sizeof(int32_t));
     l.inv = take(P * sizeof(int32_t));
     l.tiles = take((size_t)max_tiles_for(c) * sizeof(moe_tile));

@@ -551,7 +551,8 @@ int launch_by_tile_rows(int tile_rows, const GemmArgs &g, const moe_tile *tiles,
 int expected_tiles(const moe_config &c)
 {
     const long pairs = (long)c.T * c.top_k;
-    return (int)(pairs < c.E ? pairs : c.E);
+    const int el = local_experts(c);
+    return (int)(pairs < el ? pairs : el);
 }
 
 // Number of distinct K-loop starting points for rows of `row_bytes` bytes: every K step its own

@@ -33,6 +33,9 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// Experts whose weights a call holds (local-expert mode), and the first of them.
+__host__ __device__ inline int local_experts(const moe_config &c) { return c.num_local_experts > 0 ? c.num_local_experts : c.E; }
+
 // ---- launch helpers ----------------------------------------------------------
 void set_last_hip_error(hipError_t e);
 inline int check_launch()

@@ -29,8 +29,10 @@ __device__ inline void block_inclusive_scan(int *a, int *b, int n, int tid)
     }
 }
 
+// E is the number of experts that own a segment (the local ones); a pair's segment is
+// ids[p] - e_first, and pairs outside [0, E) after that shift are dropped.
 __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__restrict__ ids, int P, int E,
-                                                             int tile_rows, int max_tiles,
+                                                             int e_first, int tile_rows, int max_tiles,
                                                              int32_t *__restrict__ offsets,
                                                              int32_t *__restrict__ sorted_pair,
                                                              int32_t *__restrict__ inv,
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
 
     // pass 1: histogram of this wavefront's slice (integer LDS adds: order-independent)
     for (int p = p_beg + lane; p < p_end; p += kWave) {
-        const int e = ids[p];
+        const int e = ids[p] - e_first;
         if (e >= 0 && e < E) atomicAdd(&wcount[wave * E + e], 1);
     }
     __syncthreads();
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
     const int ebits = 32 - __clz(max(E - 1, 1));
     for (int base = p_beg; base < p_end; base += kWave) {
         const int p = base + lane;
-        const int e = (p < p_end) ? ids[p] : -1;
+        const int e = (p < p_end) ? ids[p] - e_first : -1;
         const bool valid = e >= 0 && e < E;
         unsigned long long same = __ballot(valid);
         for (int b = 0; b < ebits; ++b) {
@@ -131,8 +133,10 @@ int launch_permute(const moe_config &c, int tile_rows, int max_tiles, const int3
                    int32_t *ntiles, hipStream_t s)
 {
     const int P = c.T * c.top_k;
-    const size_t lds = sizeof(int) * ((size_t)PM_WAVES * c.E + 3 * (size_t)c.E + 1);
-    hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PM_THREADS), lds, s, ids, P, c.E, tile_rows, max_tiles,
+    const int el = local_experts(c);
+    const size_t lds = sizeof(int) * ((size_t)PM_WAVES * el + 3 * (size_t)el + 1);
+    hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PM_THREADS), lds, s, ids, P, el, c.local_expert_offset,
+                       tile_rows, max_tiles,
                        offsets, sorted_pair, inv, tiles, ntiles);
     return check_launch();
 }

@@ -47,6 +47,13 @@ class Workload:
     fp8: bool = False
     hot_experts: int = 0        # skew variant: this many experts get +hot_bias
     hot_bias: float = 0.0
+    local_offset: int = 0       # local-expert mode: first expert whose weights are held ...
+    local_experts: int = 0      # ... and how many (0 = all E)
+
+    @property
+    def EL(self) -> int:
+        """Experts whose weights the call holds."""
+        return self.local_experts if self.local_experts > 0 else self.E
 
     def replace(self, **kw) -> "Workload":
         return dataclasses.replace(self, **kw)
@@ -63,6 +70,9 @@ WORKLOADS: Dict[str, Workload] = {
     "dsv3_prefill_skew": Workload("dsv3_prefill_skew", T=4096, hot_experts=16,
                                   hot_bias=0.5, **_DSV3),
     "fp8_prefill": Workload("fp8_prefill", T=1024, fp8=True, **_DSV3),
+    # one device's share under 8-way expert parallelism: 32 local experts of 256 (the shape of the
+    # paper's Sec. 4.5 workload); experts 96..127 are group 3 of the 8 routing groups
+    "fp8_local32": Workload("fp8_local32", T=4096, fp8=True, local_offset=96, local_experts=32, **_DSV3),
 }
 
 # tensor ids for the per-tensor generator streams
@@ -123,16 +133,24 @@ class MoEInputs:
     x: torch.Tensor                       # [T,H] bf16, or fp8 e4m3fn when wl.fp8
     router_w: torch.Tensor                # [E,H] fp32
     bias: Optional[torch.Tensor]          # [E] fp32 or None
-    w1: torch.Tensor                      # [E,2I,H] bf16 / fp8 ; rows [0,I) gate, [I,2I) up
-    w2: torch.Tensor                      # [E,H,I]  bf16 / fp8
+    w1: torch.Tensor                      # [EL,2I,H] bf16 / fp8 ; rows [0,I) gate, [I,2I) up
+    w2: torch.Tensor                      # [EL,H,I]  bf16 / fp8
     x_scale: Optional[torch.Tensor] = None    # [T,H/128] fp32
-    w1_scale: Optional[torch.Tensor] = None   # [E,2I/128,H/128] fp32
-    w2_scale: Optional[torch.Tensor] = None   # [E,H/128,I/128] fp32
+    w1_scale: Optional[torch.Tensor] = None   # [EL,2I/128,H/128] fp32
+    w2_scale: Optional[torch.Tensor] = None   # [EL,H/128,I/128] fp32
 
     def to(self, device) -> "MoEInputs":
         mv = lambda t: None if t is None else t.to(device)
         return MoEInputs(self.wl, mv(self.x), mv(self.router_w), mv(self.bias), mv(self.w1),
                          mv(self.w2), mv(self.x_scale), mv(self.w1_scale), mv(self.w2_scale))
+
+    def local_share(self, offset: int, count: int) -> "MoEInputs":
+        """The same layer call as seen by a device that holds only experts [offset, offset+count)."""
+        assert self.wl.local_experts == 0 and 0 <= offset and offset + count <= self.wl.E
+        cut = lambda t: None if t is None else t[offset:offset + count].contiguous()
+        wl = self.wl.replace(name=f"{self.wl.name}_local{offset}+{count}", local_offset=offset, local_experts=count)
+        return MoEInputs(wl, self.x, self.router_w, self.bias, cut(self.w1), cut(self.w2), self.x_scale,
+                         cut(self.w1_scale), cut(self.w2_scale))
 
 
 def make_inputs(wl: Workload, seed: int = 0, device="cpu",
@@ -145,7 +163,9 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu",
     hidden ~ N(0,1); router W ~ N(0,1/H) fp32; expert weights ~ N(0,1/fan_in);
     bias ~ U(-0.1,0.1) (+hot_bias on the hot experts).  bf16 workloads round to
     bf16; fp8 workloads block-quantise (1x128 activations, 128x128 weights).
-    Expert weights are drawn one expert at a time to bound the fp32 temporaries.
+    Expert weights are drawn one expert at a time to bound the fp32 temporaries; in
+    local-expert mode only the local experts are kept (every expert is still drawn, so a
+    local share holds the same values as the corresponding slice of the full draw).
     """
     dev = torch.device(device)
     T, H, I, E = wl.T, wl.H, wl.I, wl.E
@@ -164,25 +184,28 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu",
         x, x_scale = x32.to(torch.bfloat16), None
     if weights_from is not None:
         o = weights_from
-        assert (o.wl.H, o.wl.I, o.wl.E, o.wl.fp8) == (H, I, E, wl.fp8) and o.w1.device.type == dev.type
+        assert (o.wl.H, o.wl.I, o.wl.E, o.wl.fp8, o.wl.local_offset, o.wl.local_experts) == \
+            (H, I, E, wl.fp8, wl.local_offset, wl.local_experts) and o.w1.device.type == dev.type
         return MoEInputs(wl, x, o.router_w, bias, o.w1, o.w2, x_scale, o.w1_scale, o.w2_scale)
     wdt = torch.float8_e4m3fn if wl.fp8 else torch.bfloat16
-    w1 = torch.empty((E, 2 * I, H), dtype=wdt, device=dev)
-    w2 = torch.empty((E, H, I), dtype=wdt, device=dev)
+    EL, lo = wl.EL, wl.local_offset
+    w1 = torch.empty((EL, 2 * I, H), dtype=wdt, device=dev)
+    w2 = torch.empty((EL, H, I), dtype=wdt, device=dev)
     w1_scale = w2_scale = None
     if wl.fp8:
-        w1_scale = torch.empty((E, 2 * I // QBLOCK, H // QBLOCK), dtype=torch.float32, device=dev)
-        w2_scale = torch.empty((E, H // QBLOCK, I // QBLOCK), dtype=torch.float32, device=dev)
+        w1_scale = torch.empty((EL, 2 * I // QBLOCK, H // QBLOCK), dtype=torch.float32, device=dev)
+        w2_scale = torch.empty((EL, H // QBLOCK, I // QBLOCK), dtype=torch.float32, device=dev)
     g1 = _gen(seed, _TID["w1"], dev)
     g2 = _gen(seed, _TID["w2"], dev)
-    for e in range(E):
+    for e in range(lo + EL):
         a = _normal((2 * I, H), H ** -0.5, g1, dev)
         b = _normal((H, I), I ** -0.5, g2, dev)
-        if wl.fp8:
-            w1[e], w1_scale[e] = quantize_blocks_128x128(a)
-            w2[e], w2_scale[e] = quantize_blocks_128x128(b)
-        else:
-            w1[e] = a.to(torch.bfloat16)
-            w2[e] = b.to(torch.bfloat16)
+        if e >= lo:
+            if wl.fp8:
+                w1[e - lo], w1_scale[e - lo] = quantize_blocks_128x128(a)
+                w2[e - lo], w2_scale[e - lo] = quantize_blocks_128x128(b)
+            else:
+                w1[e - lo] = a.to(torch.bfloat16)
+                w2[e - lo] = b.to(torch.bfloat16)
         del a, b
     return MoEInputs(wl, x, router_w, bias, w1, w2, x_scale, w1_scale, w2_scale)

@@ -91,10 +91,25 @@ def choice_keys(p, z):
     return s
 
 
+def local_permute(ids, E, local_offset=0, local_count=0):
+    """Oracle sort-scatter of the pairs whose expert is held locally (all of them unless
+    local-expert mode is on): offsets [EL+1], sorted_pair [kept], inv [P] with -1 for the
+    pairs that were dropped, and the number of kept pairs."""
+    flat = np.asarray(ids, dtype=np.int32).reshape(-1)
+    if local_count <= 0:
+        local_offset, local_count = 0, E
+    keep = (flat >= local_offset) & (flat < local_offset + local_count)
+    kept_pairs = np.nonzero(keep)[0].astype(np.int32)
+    off, sp, inv_k = orc.permute((flat[keep] - local_offset).reshape(-1, 1), local_count)
+    inv = np.full(flat.shape, -1, dtype=np.int32)
+    inv[keep] = inv_k
+    return off, kept_pairs[sp], inv, int(keep.sum())
+
+
 def oracle_all(inp):
     """Oracle routing for every token + the permutation of that routing."""
     p = orc.problem_from_inputs(inp)
     z = orc.router_logits(p)
     ids, w, margin = orc.route(p, z)
-    offsets, sorted_pair, inv = orc.permute(ids, p.E)
+    offsets, sorted_pair, inv, _ = local_permute(ids, p.E, p.local_offset, p.local_count)
     return p, ids, w, margin, offsets, sorted_pair, inv, choice_keys(p, z)

@@ -13,7 +13,8 @@ import torch
 from oracle import moe_oracle as orc
 from paper_2602_19128_amd import binding as moe
 from paper_2602_19128_amd import synthetic as syn
-from parity_util import TOL_MAX, TOL_MEAN, check_tiles, choice_keys, compare_routing, err_stats, f64
+from parity_util import (TOL_MAX, TOL_MEAN, check_tiles, choice_keys, compare_routing, err_stats, f64,
+                         local_permute)
 
 pytestmark = pytest.mark.gpu
 
@@ -48,9 +49,9 @@ def _check_workload(gpu, host_w, sample_tokens=SAMPLE_TOKENS):
                                                choice_keys(p, z))
     off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_g)
     torch.cuda.synchronize()
-    off_r, sp_r, inv_r = orc.permute(ids_g.cpu().numpy(), wl.E)      # oracle on the GPU's own routing
+    off_r, sp_r, inv_r, kept = local_permute(ids_g.cpu().numpy(), wl.E, wl.local_offset, wl.local_experts)   # oracle on the GPU's own routing
     assert np.array_equal(off_g.cpu().numpy(), off_r)
-    assert np.array_equal(sp_g.cpu().numpy(), sp_r) and np.array_equal(inv_g.cpu().numpy(), inv_r)
+    assert np.array_equal(sp_g.cpu().numpy()[:kept], sp_r) and np.array_equal(inv_g.cpu().numpy(), inv_r)
     check_tiles(tiles, ntiles, off_r, moe.moe_tile_rows(cfg))
     load = np.diff(off_r)
     print(f"  routing: tie-excused tokens={other} swapped slots={swapped} of {wl.T}; "
@@ -58,7 +59,12 @@ def _check_workload(gpu, host_w, sample_tokens=SAMPLE_TOKENS):
 
     # layer output on sampled tokens
     rng = np.random.default_rng(0)
-    sample = np.sort(rng.choice(wl.T, size=min(sample_tokens, wl.T), replace=False)).astype(np.int32)
+    cand = np.arange(wl.T)
+    if wl.local_experts > 0:      # tokens with at least one expert held here (the others are exactly zero)
+        local = (ids_r >= wl.local_offset) & (ids_r < wl.local_offset + wl.local_experts)
+        assert not f64(out[torch.from_numpy(np.nonzero(~local.any(axis=1) & same_set)[0]).cuda()]).any()
+        cand = np.nonzero(local.any(axis=1))[0]
+    sample = np.sort(rng.choice(cand, size=min(sample_tokens, len(cand)), replace=False)).astype(np.int32)
     ref, ids_s, w_s, margin_s = orc.forward_tokens(p, sample)
     keep = same_set[sample]
     got = f64(out[torch.from_numpy(sample.astype(np.int64)).cuda()])
@@ -90,4 +96,10 @@ def test_dsv3_full_size(dsv3, name):
 
 def test_fp8_prefill_full_size():
     gpu = syn.make_inputs(syn.WORKLOADS["fp8_prefill"], seed=0, device="cuda")
+    _check_workload(gpu, gpu.to("cpu"))
+
+
+def test_fp8_local_experts_full_size():
+    """One device's share of the DeepSeek-V3-shaped layer: 32 local experts of 256."""
+    gpu = syn.make_inputs(syn.WORKLOADS["fp8_local32"], seed=0, device="cuda")
     _check_workload(gpu, gpu.to("cpu"))

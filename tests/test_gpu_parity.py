@@ -35,6 +35,12 @@ CASES = {
     "fp8_grouped": syn.Workload("fp8_grouped", T=96, H=512, I=256, E=256, top_k=8, n_group=8,
                                 topk_group=4, fp8=True, **GROUPED),
     "fp8_tall": syn.Workload("fp8_tall", T=700, H=384, I=128, E=4, top_k=2, fp8=True),   # several 256-row tiles
+    # local-expert mode: only a slice of the experts has weights here, the other pairs are dropped
+    "local_bf16": syn.Workload("local_bf16", T=90, H=256, I=128, E=16, top_k=4, local_offset=4, local_experts=8),
+    "local_fp8": syn.Workload("local_fp8", T=120, H=256, I=256, E=32, top_k=6, n_group=4, topk_group=2, fp8=True,
+                              local_offset=16, local_experts=8, **GROUPED),
+    # the limits of the interface: 512 experts (8 per lane in the router) and 64 experts per token
+    "max_experts": syn.Workload("max_experts", T=40, H=128, I=64, E=512, top_k=64),
 }
 
 
@@ -64,7 +70,7 @@ def test_permute(case):
     off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_d)
     torch.cuda.synchronize()
     assert np.array_equal(off_g.cpu().numpy(), offsets)
-    assert np.array_equal(sp_g.cpu().numpy(), sorted_pair)
+    assert np.array_equal(sp_g.cpu().numpy()[: len(sorted_pair)], sorted_pair)      # rows of the kept pairs
     assert np.array_equal(inv_g.cpu().numpy(), inv)
     n = check_tiles(tiles, ntiles, offsets, moe.moe_tile_rows(cfg))
     assert n <= moe.moe_max_tiles(cfg)
@@ -75,8 +81,8 @@ def _staged(case):
     cfg = moe.MoEConfig.from_workload(wl)
     ids_d = torch.from_numpy(ids).cuda()
     off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_d)
-    tok = sorted_pair // wl.top_k
-    exp = ids.reshape(-1)[sorted_pair]
+    tok = sorted_pair // wl.top_k                            # one entry per kept pair, in sorted-row order
+    exp = ids.reshape(-1)[sorted_pair] - wl.local_offset     # index into the (local) weight arrays
     return wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv
 
 
@@ -93,13 +99,15 @@ def test_gemm_swiglu(case):
     act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
     torch.cuda.synchronize()
     ref = orc.swiglu_rows(p, tok, exp)
+    n = len(tok)                                             # rows beyond the kept pairs are never written
+    act_g, sc_g = act_g[:n], (None if sc_g is None else sc_g[:n])
     max_rel, mean_rel = err_stats(_act_f64(act_g, sc_g), ref)
     print(f"swiglu {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e}")
     if wl.fp8:
         # re-quantised to e4m3 (3 mantissa bits) per 1x128 block with scale = amax/448
         assert max_rel <= 2 ** -4 + 1e-3 and mean_rel <= 3.5e-2
-        q = act_g.float().abs().reshape(cfg.P, -1, 128).amax(dim=-1)
-        amax_ref = torch.from_numpy(np.abs(ref).reshape(cfg.P, -1, 128).max(axis=-1)).cuda()
+        q = act_g.float().abs().reshape(n, -1, 128).amax(dim=-1)
+        amax_ref = torch.from_numpy(np.abs(ref).reshape(n, -1, 128).max(axis=-1)).cuda()
         assert ((q == 448) | (amax_ref == 0)).all(), "every non-zero block must use the full e4m3 range"
         np.testing.assert_allclose(sc_g.cpu().numpy(), np.maximum(amax_ref.cpu().numpy(), 1e-30) / 448, rtol=1e-2)
     else:
@@ -111,8 +119,9 @@ def test_gemm_down(case):
     act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
     y_g = moe.moe_grouped_gemm_down(cfg, act_g, sc_g, gpu.w2, gpu.w2_scale, tiles, ntiles)
     torch.cuda.synchronize()
-    ref = orc.down_rows(p, exp, _act_f64(act_g, sc_g))   # from the very activations the GPU consumed
-    max_rel, mean_rel = err_stats(f64(y_g), ref)
+    n = len(tok)
+    ref = orc.down_rows(p, exp, _act_f64(act_g[:n], None if sc_g is None else sc_g[:n]))   # from the very activations the GPU consumed
+    max_rel, mean_rel = err_stats(f64(y_g[:n]), ref)
     print(f"down {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e}")
     assert max_rel <= 6e-3 and mean_rel <= 3e-3
 

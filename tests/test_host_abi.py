@@ -70,6 +70,9 @@ def test_size_queries_and_tile_heights(lib):
     (dict(n_group=4, topk_group=5), -1),
     (dict(n_group=4, topk_group=1, group_score_topn=2, top_k=3), -1),   # top_k > eligible experts
     (dict(n_group=4, topk_group=2, group_score_topn=3), -1),            # topn > group size
+    (dict(local_expert_offset=4, num_local_experts=5), -1),             # local range past the last expert
+    (dict(local_expert_offset=2, num_local_experts=0), -1),             # offset without a local count
+    (dict(num_local_experts=-1), -1),
 ])
 def test_bad_problem_statements_are_refused(lib, change, code):
     cfg = moe.MoEConfig(T=16, H=256, I=128, E=8, top_k=2, scoring=0, renormalize=1, n_group=1,

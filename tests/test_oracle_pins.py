@@ -381,3 +381,48 @@ def test_fp8_quantised_inputs_are_close_to_their_source():
     deq = q.float() * s.repeat_interleave(128, dim=1)
     assert ((deq - v).abs() <= v.abs() * 2 ** -4 + s.repeat_interleave(128, dim=1) * 2 ** -10 + 1e-12).all()
     assert q.float().abs().max() <= 448
+
+
+# ---------------------------------------------------------------- local-expert mode
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_local_shares_partition_the_layer(fp8):
+    """Disjoint local ranges that cover every expert add up to the full layer, a range that
+    holds none of a token's experts gives exactly zero, the full range changes nothing."""
+    wl = _wl(T=9, H=128, I=128, E=8, top_k=3, fp8=fp8)
+    full = syn.make_inputs(wl, seed=5)
+    p = orc.problem_from_inputs(full)
+    ref, ids, w, margin = orc.forward(p)
+    total = np.zeros_like(ref)
+    for lo, n in [(0, 3), (3, 1), (4, 4)]:
+        share = full.local_share(lo, n)
+        out, ids_s, w_s, _ = orc.forward(orc.problem_from_inputs(share))
+        assert np.array_equal(ids_s, ids) and np.array_equal(w_s, w)        # routing is that of the full layer
+        total += out
+        untouched = ~((ids >= lo) & (ids < lo + n)).any(axis=1)
+        assert (out[untouched] == 0).all()
+        # brute force over the token's chosen experts with the full weights
+        for t in range(wl.T):
+            acc = np.zeros(wl.H)
+            for j in range(wl.top_k):
+                e = int(ids[t, j])
+                if lo <= e < lo + n:
+                    act = orc.swiglu_rows(p, [t], [e])
+                    acc += w[t, j] * orc.down_rows(p, [e], act)[0]
+            np.testing.assert_allclose(out[t], acc, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(total, ref, rtol=1e-12, atol=1e-13)
+    same, *_ = orc.forward(orc.problem_from_inputs(full.local_share(0, wl.E)))
+    assert np.array_equal(same, ref)
+
+
+def test_combine_skips_pairs_without_a_row():
+    rng = np.random.default_rng(2)
+    T, k, H = 5, 3, 4
+    w = rng.normal(size=(T, k))
+    y = rng.normal(size=(T * k, H))
+    inv = rng.permutation(T * k).astype(np.int32)
+    dropped = np.array([1, 4, 5, 13])
+    inv_d = inv.copy(); inv_d[dropped] = -1
+    w_zero = w.copy().reshape(-1); w_zero[dropped] = 0.0
+    np.testing.assert_allclose(orc.combine(w, inv_d, y), orc.combine(w_zero.reshape(T, k), inv, y), rtol=0, atol=0)
