@@ -141,6 +141,185 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const void *__restri
     }
 }
 
+// ---- many tokens: logits on the matrix cores ---------------------------------------------------
+//
+// The fp32 router weights are split once per call into three bf16 planes, w = hi + mid + lo
+// (each the bf16 rounding of what the previous ones leave; together they carry the 24-bit
+// mantissa), so that x . w = x.hi + x.mid + x.lo with bf16 MFMAs: the hidden states are bf16 (or
+// fp8 payloads, exact in bf16), every product is exact in fp32 and the sums accumulate in fp32,
+// which keeps the logits at fp32 accuracy - a routing decision is only allowed to differ from an
+// exact evaluation when its margin is below 1e-6.
+//
+// A workgroup of 8 wavefronts owns TB*16 tokens x 256 experts x one slice of H.  Wavefront w owns
+// expert blocks 2w, 2w+1 (16 experts each) against all token blocks; per 32-wide K step the
+// workgroup stages the token rows and the three weight planes in LDS (double buffered, loads of
+// the next step in registers while the MFMAs of the current one run).  fp8 inputs: the payload is
+// multiplied as is and each 128-wide block's sum is folded in with the token's block scale.
+typedef __attribute__((ext_vector_type(8))) __bf16 rt_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float rt_f32x4;
+
+constexpr int RM_BE = 256;                 // experts per workgroup tile
+constexpr int RM_BK = 32;                  // hidden elements per K step (one MFMA deep)
+constexpr int RM_THREADS = 512;
+constexpr int RM_MIN_TOKENS = 512;         // below this the FMA kernel's finer tiles fill the chip better
+
+__global__ __launch_bounds__(256) void router_split_weights_kernel(const float *__restrict__ w, uint16_t *__restrict__ planes,
+                                                                   size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float v = w[i];
+    const uint32_t hi = f32_to_bf16_bits(v);
+    const float r1 = v - bf16_bits_to_f32(hi);
+    const uint32_t mid = f32_to_bf16_bits(r1);
+    const float r2 = r1 - bf16_bits_to_f32(mid);
+    const uint32_t lo = f32_to_bf16_bits(r2);
+    planes[i] = (uint16_t)hi;
+    planes[n + i] = (uint16_t)mid;
+    planes[2 * n + i] = (uint16_t)lo;
+}
+
+// 8 fp8 e4m3 payload bytes -> 8 bf16 (exact).
+__device__ inline uint4 fp8x8_to_bf16x8(uint2 raw)
+{
+    uint4 o;
+    o.x = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.x, 0), __builtin_amdgcn_cvt_f32_fp8(raw.x, 1));
+    o.y = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.x, 2), __builtin_amdgcn_cvt_f32_fp8(raw.x, 3));
+    o.z = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.y, 0), __builtin_amdgcn_cvt_f32_fp8(raw.y, 1));
+    o.w = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.y, 2), __builtin_amdgcn_cvt_f32_fp8(raw.y, 3));
+    return o;
+}
+
+template <bool FP8, int TB>
+__global__ __launch_bounds__(RM_THREADS) void router_logits_mfma_kernel(const void *__restrict__ x,
+                                                                        const float *__restrict__ x_scale,
+                                                                        const uint16_t *__restrict__ planes,
+                                                                        float *__restrict__ zpart, int T, int H, int E,
+                                                                        int k_per_split)
+{
+    constexpr int BT = TB * 16;                            // tokens per workgroup
+    constexpr int X_BYTES = BT * RM_BK * 2;                // one stage of token rows (bf16)
+    constexpr int W_BYTES = 3 * RM_BE * RM_BK * 2;         // one stage of the three planes
+    constexpr int STAGE = X_BYTES + W_BYTES;
+    constexpr int XV = BT * 4 / RM_THREADS;                // 16-byte pieces of x per thread and stage (2 or 1)
+    constexpr int WV = 3 * RM_BE * 4 / RM_THREADS;         // 16-byte pieces of the planes per thread and stage (6)
+    static_assert(XV >= 1 && BT * 4 % RM_THREADS == 0, "token tile must give every thread whole pieces");
+    extern __shared__ __align__(16) unsigned char rsm[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int t0 = blockIdx.x * BT, e0 = blockIdx.y * RM_BE;
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = min(H, kbeg + k_per_split);
+    const int nsteps = (kend - kbeg) / RM_BK;              // H and the split size are multiples of 32
+    const size_t plane = (size_t)E * H;
+
+    // loader coordinates: piece v of this thread is row (tid + v*512) / 4, 16-byte chunk (tid + v*512) % 4
+    uint4 xr[XV], wr[WV];
+    auto load_stage = [&](int step) {
+        const int k0 = kbeg + step * RM_BK;
+#pragma unroll
+        for (int v = 0; v < XV; ++v) {
+            const int idx = tid + v * RM_THREADS, row = idx >> 2, ch = idx & 3;
+            const int t = t0 + row;
+            if (t < T) {
+                if constexpr (FP8) {
+                    const uint2 raw = *reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(x) + (size_t)t * H + k0 + ch * 8);
+                    xr[v] = fp8x8_to_bf16x8(raw);
+                } else {
+                    xr[v] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(x) + (size_t)t * H + k0 + ch * 8);
+                }
+            } else {
+                xr[v] = uint4{0u, 0u, 0u, 0u};
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < WV; ++v) {
+            const int idx = tid + v * RM_THREADS, pl = idx / (RM_BE * 4), row = (idx >> 2) % RM_BE, ch = idx & 3;
+            const int e = e0 + row;
+            wr[v] = e < E ? *reinterpret_cast<const uint4 *>(planes + pl * plane + (size_t)e * H + k0 + ch * 8)
+                          : uint4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_stage = [&](int buf) {
+        unsigned char *xs = rsm + buf * STAGE, *ws = xs + X_BYTES;
+#pragma unroll
+        for (int v = 0; v < XV; ++v) *reinterpret_cast<uint4 *>(xs + (tid + v * RM_THREADS) * 16) = xr[v];
+#pragma unroll
+        for (int v = 0; v < WV; ++v) *reinterpret_cast<uint4 *>(ws + (tid + v * RM_THREADS) * 16) = wr[v];
+    };
+
+    rt_f32x4 acc[2][TB];
+    rt_f32x4 blk[FP8 ? 2 : 1][FP8 ? TB : 1];               // fp8: sum of the current 128-wide scale block
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int m = 0; m < TB; ++m) {
+            acc[b][m] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (FP8) blk[b][m] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+
+    load_stage(0);
+    store_stage(0);
+    __syncthreads();
+    for (int s = 0; s < nsteps; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < nsteps) load_stage(s + 1);             // in registers while this step computes
+        const unsigned char *xs = rsm + buf * STAGE, *ws = xs + X_BYTES;
+        rt_bf16x8 wf[2][3];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                wf[b][pl] = *reinterpret_cast<const rt_bf16x8 *>(ws + ((pl * RM_BE + (wave * 2 + b) * 16 + l16) * 4 + lq) * 16);
+#pragma unroll
+        for (int m = 0; m < TB; ++m) {
+            const rt_bf16x8 tf = *reinterpret_cast<const rt_bf16x8 *>(xs + ((m * 16 + l16) * 4 + lq) * 16);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                rt_f32x4 &dst = FP8 ? blk[b][m] : acc[b][m];
+                // smallest plane first: the small contributions meet before the large one is added
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[b][2], tf, dst, 0, 0, 0);
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[b][1], tf, dst, 0, 0, 0);
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[b][0], tf, dst, 0, 0, 0);
+            }
+        }
+        if constexpr (FP8) {
+            const int k0 = kbeg + s * RM_BK;
+            if ((k0 + RM_BK) % kQBlock == 0 || s + 1 == nsteps) {      // a scale block ends here
+#pragma unroll
+                for (int m = 0; m < TB; ++m) {
+                    const int t = t0 + m * 16 + l16;
+                    const float sc = t < T ? x_scale[(size_t)t * (H / kQBlock) + k0 / kQBlock] : 0.f;
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[b][m][v] = fmaf(blk[b][m][v], sc, acc[b][m][v]);
+                        blk[b][m] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+            }
+        }
+        if (s + 1 < nsteps) store_stage(buf ^ 1);          // that buffer was last read in step s-1
+        __syncthreads();
+    }
+
+    // lane (l16, lq) holds, per expert block, experts 4*lq..4*lq+3 of token l16 of each token block
+    float *dst = zpart + (size_t)blockIdx.z * T * E;
+#pragma unroll
+    for (int m = 0; m < TB; ++m) {
+        const int t = t0 + m * 16 + l16;
+        if (t >= T) continue;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int e = e0 + (wave * 2 + b) * 16 + lq * 4;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (e + v < E) dst[(size_t)t * E + e + v] = acc[b][m][v];
+        }
+    }
+}
+
 // ---- cross-lane helpers -------------------------------------------------------
 
 // Monotone map fp32 -> uint32 (larger float <=> larger integer).
@@ -382,8 +561,35 @@ __global__ __launch_bounds__(256) void router_few_experts_kernel(const void *__r
 
 }  // namespace
 
+// Matrix-core path: token tile height (in 16-row blocks) and H split.
+struct MfmaGrid { bool use; int tb, tiles_t, tiles_e, splits, k_per_split; };
+
+MfmaGrid mfma_grid(const moe_config &c)
+{
+    MfmaGrid g{};
+    g.use = c.T >= RM_MIN_TOKENS && c.E > RT_FEW && c.H % RM_BK == 0;
+    if (!g.use) return g;
+    g.tb = c.dtype == MOE_DTYPE_FP8_E4M3 ? 8 : 16;         // fp8 keeps a second accumulator set per scale block
+    g.tiles_t = ceil_div(c.T, g.tb * 16);
+    g.tiles_e = ceil_div(c.E, RM_BE);
+    const int chunks = c.H / RM_BK;
+    int want = ceil_div(256, g.tiles_t * g.tiles_e);       // one workgroup per compute unit
+    if (want > RT_MAX_SPLIT) want = RT_MAX_SPLIT;
+    if (want > chunks) want = chunks;
+    if (want < 1) want = 1;
+    int per = ceil_div(chunks, want) * RM_BK;
+    if (c.dtype == MOE_DTYPE_FP8_E4M3) per = ceil_div(per, kQBlock) * kQBlock;   // splits end on scale-block edges
+    g.k_per_split = per;
+    g.splits = ceil_div(c.H, per);
+    return g;
+}
+
 size_t route_workspace_bytes(const moe_config &c)
 {
+    if (c.E <= RT_FEW) return 256;
+    const MfmaGrid m = mfma_grid(c);
+    if (m.use)
+        return align_up((size_t)m.splits * c.T * c.E * sizeof(float), 256) + align_up((size_t)3 * c.E * c.H * 2, 256);
     const RouteGrid g = route_grid(c);
     return align_up((size_t)g.splits * c.T * c.E * sizeof(float), 256);
 }
@@ -403,19 +609,59 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
                                ids, w, p, c.H);
         return check_launch();
     }
-    const RouteGrid g = route_grid(c);
     float *zpart = static_cast<float *>(ws);
-    const dim3 grid(g.tiles_t, g.tiles_e, g.splits);
-    if (c.dtype == MOE_DTYPE_FP8_E4M3)
-        hipLaunchKernelGGL(router_logits_kernel<true>, grid, dim3(256), 0, s, x, x_scale, router_w, zpart,
-                           c.T, c.H, c.E, g.k_per_split);
-    else
-        hipLaunchKernelGGL(router_logits_kernel<false>, grid, dim3(256), 0, s, x, x_scale, router_w, zpart,
-                           c.T, c.H, c.E, g.k_per_split);
-    int rc = check_launch();
-    if (rc != MOE_OK) return rc;
+    const MfmaGrid m = mfma_grid(c);
+    if (m.use) {
+        uint16_t *planes = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(ws) +
+                                                        align_up((size_t)m.splits * c.T * c.E * sizeof(float), 256));
+        const size_t n = (size_t)c.E * c.H;
+        hipLaunchKernelGGL(router_split_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, router_w,
+                           planes, n);
+        int rc = check_launch();
+        if (rc != MOE_OK) return rc;
+        const dim3 grid(m.tiles_t, m.tiles_e, m.splits);
+        if (c.dtype == MOE_DTYPE_FP8_E4M3) {
+            auto kern = router_logits_mfma_kernel<true, 8>;
+            constexpr int lds = 2 * (8 * 16 * RM_BK * 2 + 3 * RM_BE * RM_BK * 2);
+            static bool attr_done = false;
+            if (!attr_done) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
+                attr_done = true;
+            }
+            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, planes, zpart, c.T, c.H, c.E,
+                               m.k_per_split);
+        } else {
+            auto kern = router_logits_mfma_kernel<false, 16>;
+            constexpr int lds = 2 * (16 * 16 * RM_BK * 2 + 3 * RM_BE * RM_BK * 2);
+            static bool attr_done = false;
+            if (!attr_done) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
+                attr_done = true;
+            }
+            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, planes, zpart, c.T, c.H, c.E,
+                               m.k_per_split);
+        }
+        rc = check_launch();
+        if (rc != MOE_OK) return rc;
+        p.splits = m.splits;
+    } else {
+        const RouteGrid g = route_grid(c);
+        const dim3 grid(g.tiles_t, g.tiles_e, g.splits);
+        if (c.dtype == MOE_DTYPE_FP8_E4M3)
+            hipLaunchKernelGGL(router_logits_kernel<true>, grid, dim3(256), 0, s, x, x_scale, router_w, zpart,
+                               c.T, c.H, c.E, g.k_per_split);
+        else
+            hipLaunchKernelGGL(router_logits_kernel<false>, grid, dim3(256), 0, s, x, x_scale, router_w, zpart,
+                               c.T, c.H, c.E, g.k_per_split);
+        int rc = check_launch();
+        if (rc != MOE_OK) return rc;
+        p.splits = g.splits;
+    }
 
-    p.splits = g.splits;
     const dim3 tgrid(ceil_div(c.T, 4));
     const int epl = c.E <= 64 ? 1 : c.E <= 128 ? 2 : c.E <= 256 ? 4 : 8;
     switch (epl) {

@@ -39,6 +39,10 @@ CASES = {
     "local_bf16": syn.Workload("local_bf16", T=90, H=256, I=128, E=16, top_k=4, local_offset=4, local_experts=8),
     "local_fp8": syn.Workload("local_fp8", T=120, H=256, I=256, E=32, top_k=6, n_group=4, topk_group=2, fp8=True,
                               local_offset=16, local_experts=8, **GROUPED),
+    # enough tokens for the matrix-core router (ragged token tile, expert count not a multiple of 16)
+    "many_tokens": syn.Workload("many_tokens", T=600, H=256, I=64, E=40, top_k=4),
+    "many_tokens_fp8": syn.Workload("many_tokens_fp8", T=530, H=384, I=128, E=64, top_k=6, n_group=4, topk_group=3,
+                                    fp8=True, **GROUPED),
     # the limits of the interface: 512 experts (8 per lane in the router) and 64 experts per token
     "max_experts": syn.Workload("max_experts", T=40, H=128, I=64, E=512, top_k=64),
 }
