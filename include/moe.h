@@ -112,9 +112,10 @@ int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const 
  *   offsets_out  [EL+1] int32, first sorted row of each local expert; offsets[EL] = kept pairs
  *   sorted_pair_out [P] int32, pair stored at each sorted row (ascending p inside an expert)
  *   inv_out      [P] int32, sorted row of each pair (-1 for a dropped pair)
- *   tiles_out    [moe_max_tiles(cfg)] records cut at moe_tile_rows(cfg) rows, experts in
- *                ascending order, none for an expert without tokens (such experts cost
- *                nothing downstream); `expert` counts from the first local expert (it
+ *   tiles_out    [moe_max_tiles(cfg)] records of at most moe_tile_rows(cfg) rows (an expert with
+ *                more rows is cut into the fewest such tiles, of equal height rounded up to
+ *                16 rows), experts in ascending order, none for an expert without tokens
+ *                (such experts cost nothing downstream); `expert` counts from the first local expert (it
  *                indexes w1 / w2); ntiles_out [1] int32 = records written
  */
 int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,

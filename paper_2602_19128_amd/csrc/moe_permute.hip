@@ -87,11 +87,14 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
     block_inclusive_scan(scan_a, scan_b, E, tid);
     if (tid < E) {
         const int first = scan_a[tid] - my_tiles;
+        // an expert with more rows than a tile is cut into equal parts (rounded up to whole MFMA
+        // row blocks): the grouped GEMMs' step time grows with the rows of a tile
+        const int part = my_tiles > 0 ? ceil_div(ceil_div(total, my_tiles), 16) * 16 : 0;
         for (int i = 0; i < my_tiles && first + i < max_tiles; ++i) {
             moe_tile rec;
             rec.expert = tid;
-            rec.row0 = first_row[tid] + i * tile_rows;
-            rec.rows = min(tile_rows, total - i * tile_rows);
+            rec.row0 = first_row[tid] + i * part;
+            rec.rows = max(0, min(part, total - i * part));
             rec.first = first;
             rec.count = my_tiles;
             rec.pad0 = rec.pad1 = rec.pad2 = 0;

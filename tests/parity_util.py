@@ -70,9 +70,11 @@ def check_tiles(tiles, ntiles, offsets_ref, tile_rows):
         lo, hi = int(offsets_ref[e]), int(offsets_ref[e + 1])
         cnt = -(-(hi - lo) // tile_rows)
         first = len(want)
+        part = -(-(-(-(hi - lo) // cnt) if cnt else 0) // 16) * 16    # equal parts, whole 16-row blocks
         for i in range(cnt):
-            r0 = lo + i * tile_rows
-            want.append([e, r0, min(tile_rows, hi - r0), first, cnt])
+            r0 = lo + i * part
+            assert hi - r0 > 0
+            want.append([e, r0, min(part, hi - r0), first, cnt])
     assert n == len(want), f"{n} tiles, expected {len(want)}"
     if n:
         assert np.array_equal(rec[:, :5], np.array(want, dtype=np.int32))
