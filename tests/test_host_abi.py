@@ -58,7 +58,8 @@ def test_size_queries_and_tile_heights(lib):
         assert moe.moe_max_tiles(cfg) >= -(-P // rows)
         ws = moe.moe_workspace_size(cfg)
         assert ws % 256 == 0 and ws >= P * wl.I * 2 + P * wl.H * 2
-        assert moe.moe_route_workspace_size(cfg) >= wl.T * wl.E * 4
+        # partial logits [splits, T, E] fp32; layers with at most 16 experts route in one kernel without scratch
+        assert moe.moe_route_workspace_size(cfg) >= (wl.T * wl.E * 4 if wl.E > 16 else 1)
 
 
 @pytest.mark.parametrize("change, code", [
