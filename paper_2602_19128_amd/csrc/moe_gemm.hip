@@ -472,8 +472,7 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
     if constexpr (NB > SH::MB_MAX) {
         return;
     } else {
-        // row-block counts are rounded up to even above 4 to bound the number of instantiations
-        constexpr int NEXT = NB < 4 ? NB + 1 : NB + 2;
+        constexpr int NEXT = NB + 1;
         if (nb <= NB) gemm_tile<SH, NB>(g, tile, ct, work, smem);
         else dispatch_blocks<SH, NEXT>(nb, g, tile, ct, work, smem);
     }
