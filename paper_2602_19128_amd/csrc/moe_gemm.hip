@@ -86,6 +86,22 @@ __device__ __forceinline__ void copy4_to_lds(const void *g, uint32_t lds_base)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(g) : "memory");
 }
 
+// s_waitcnt vmcnt(n) for a wavefront-uniform run-time n (the instruction takes an immediate).
+__device__ __forceinline__ void wait_vmcnt_upto(int n)
+{
+    switch (n) {
+#define MOE_WAIT_CASE(k) case k: MOE_WAIT_VMCNT(k); break;
+        MOE_WAIT_CASE(0) MOE_WAIT_CASE(1) MOE_WAIT_CASE(2) MOE_WAIT_CASE(3) MOE_WAIT_CASE(4) MOE_WAIT_CASE(5)
+        MOE_WAIT_CASE(6) MOE_WAIT_CASE(7) MOE_WAIT_CASE(8) MOE_WAIT_CASE(9) MOE_WAIT_CASE(10) MOE_WAIT_CASE(11)
+        MOE_WAIT_CASE(12) MOE_WAIT_CASE(13) MOE_WAIT_CASE(14) MOE_WAIT_CASE(15) MOE_WAIT_CASE(16) MOE_WAIT_CASE(17)
+        MOE_WAIT_CASE(18) MOE_WAIT_CASE(19) MOE_WAIT_CASE(20) MOE_WAIT_CASE(21) MOE_WAIT_CASE(22) MOE_WAIT_CASE(23)
+        MOE_WAIT_CASE(24) MOE_WAIT_CASE(25) MOE_WAIT_CASE(26) MOE_WAIT_CASE(27) MOE_WAIT_CASE(28) MOE_WAIT_CASE(29)
+        MOE_WAIT_CASE(30)
+#undef MOE_WAIT_CASE
+    default: MOE_WAIT_VMCNT(0); break;                        // waiting for more than needed is always safe
+    }
+}
+
 __device__ __forceinline__ int lds_off(int row, int chunk)   // byte offset of logical 16-byte chunk of a row
 {
     return row * 128 + ((chunk ^ (row & 7)) << 4);
@@ -136,7 +152,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     constexpr int STAGE_BYTES = SH::STAGE_BYTES;
     constexpr int A_PASS_MAX = (NB * 2 + NW - 1) / NW;        // 8-row copy passes per wavefront
     constexpr int SLAB = SH::SLAB;
-    static_assert(A_PASS_MAX <= 8, "wait table below covers up to 9 extra copies per wavefront");
+    static_assert(GM_W_COPIES + (DA - 1) * (GM_W_COPIES + A_PASS_MAX + 1) <= 30, "wait_vmcnt_upto covers up to 30 copies in flight");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lets the compiler keep it scalar
@@ -228,11 +244,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[m][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Copies of K step `s`, clamped to the last step (the tail copies are dummies that keep the
-    // number of copies per slot constant, which the explicit wait counts rely on).
+    // Copies of K step `s` (callers issue them only for s < nk).
 #define MOE_COPY_TOKENS(s)                                                                             \
     {                                                                                                  \
-        const int ks_ = k_rot(min((s), nk - 1));                                                       \
+        const int ks_ = k_rot(s);                                                                      \
         const int k0_ = ks_ * GM_STEP_BYTES;                                                           \
         const uint32_t dst_ = smem_lds + ((s) % SA) * STAGE_BYTES;                                     \
         _Pragma("unroll") for (int i = 0; i < A_PASS_MAX; ++i)                                         \
@@ -245,7 +260,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     }
 #define MOE_COPY_WEIGHTS(s)                                                                            \
     {                                                                                                  \
-        const int k0_ = k_rot(min((s), nk - 1)) * GM_STEP_BYTES;                                       \
+        const int k0_ = k_rot(s) * GM_STEP_BYTES;                                                      \
         const uint32_t dst_ = w_lds + ((s) % SW) * GM_W_STAGE;                                         \
         if (share_weights) {                                                                           \
             _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                    \
@@ -260,31 +275,23 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     // prologue: slots -DW .. -1
 #pragma unroll
     for (int t = -DW; t < 0; ++t) {
-        if (t + DA >= 0) MOE_COPY_TOKENS(t + DA)
-        MOE_COPY_WEIGHTS(t + DW)
+        if (t + DA >= 0 && t + DA < nk) MOE_COPY_TOKENS(t + DA)
+        if (t + DW < nk) MOE_COPY_WEIGHTS(t + DW)
     }
 
     for (int s = 0; s < nk; ++s) {
         // Step s needs its token copy (slot s-DA) and its weight copy (slot s-DW, older or same)
         // landed.  Copies complete in order, so it is enough to let only what was issued after the
-        // younger of the two stay in flight: DA-1 complete slots, plus (when the weights run
-        // further ahead than the token rows) the weight copies sharing the slot of that token copy.
-#define MOE_WAIT_FOR_STEP(a) MOE_WAIT_VMCNT((DW > DA ? GM_W_COPIES : 0) + (DA - 1) * (GM_W_COPIES + (a)))
-        switch (a_cnt) {
-        case 0: MOE_WAIT_FOR_STEP(0); break;
-        case 1: MOE_WAIT_FOR_STEP(1); break;
-        case 2: MOE_WAIT_FOR_STEP(2); break;
-        case 3: MOE_WAIT_FOR_STEP(3); break;
-        case 4: MOE_WAIT_FOR_STEP(4); break;
-        case 5: MOE_WAIT_FOR_STEP(5); break;
-        case 6: MOE_WAIT_FOR_STEP(6); break;
-        case 7: MOE_WAIT_FOR_STEP(7); break;
-        case 8: MOE_WAIT_FOR_STEP(8); break;
-        default: MOE_WAIT_FOR_STEP(9); break;
-        }
-#undef MOE_WAIT_FOR_STEP
+        // younger of the two stay in flight: the weight copy sharing the slot of that token copy
+        // (when the weights run further ahead than the token rows) and the DA-1 slots after it.
+        // Near the end of K some of those copies do not exist; they are not counted.
+        int in_flight = (DW > DA && s - DA + DW < nk) ? GM_W_COPIES : 0;
+#pragma unroll
+        for (int t = 1 - DA; t < 0; ++t)
+            in_flight += (s + t + DA < nk ? a_cnt : 0) + (s + t + DW < nk ? GM_W_COPIES : 0);
+        wait_vmcnt_upto(in_flight);
         asm volatile("s_barrier" ::: "memory");               // token stage s complete for everyone; stage s-1 free
-        MOE_COPY_TOKENS(s + DA)
+        if (s + DA < nk) MOE_COPY_TOKENS(s + DA)
         __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sa = smem + (s % SA) * STAGE_BYTES;
         const unsigned char *sw = w_ring + (s % SW) * GM_W_STAGE;
@@ -346,7 +353,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
                 if (m == 0) {
                     // the MFMAs above waited for the weight fragments (LDS reads return in order and the
                     // token fragment was requested after them): the weight slot may be refilled
-                    MOE_COPY_WEIGHTS(s + DW)
+                    if (s + DW < nk) MOE_COPY_WEIGHTS(s + DW)
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -377,7 +384,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
                 if (q == 0) {
                     // the MFMAs above waited for all four weight fragments (LDS reads return in order and
                     // the token fragment was requested after them): the weight slot may be refilled
-                    MOE_COPY_WEIGHTS(s + DW)
+                    if (s + DW < nk) MOE_COPY_WEIGHTS(s + DW)
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -385,7 +392,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         }
         __builtin_amdgcn_sched_barrier(0);
     }
-    MOE_WAIT_VMCNT(0);                                        // dummy tail copies must not outlive the LDS rings
+    MOE_WAIT_VMCNT(0);                                        // nothing is in flight any more; cheap insurance for the LDS reuse below
 #undef MOE_COPY_TOKENS
 #undef MOE_COPY_WEIGHTS
 
