@@ -117,6 +117,7 @@ struct GemmArgs {
     float *out_scale;             // fp8 gate/up: act_scale [P, n_out/128]
     int K, n_out, top_k;
     int k_groups;                 // distinct K-loop starting points spread over the workgroups (1 = all start at 0)
+    int nt_out;                   // write the output with non-temporal stores (it is too large to stay in L2 anyway)
 };
 
 // Compile-time shape of one kernel variant.
@@ -479,9 +480,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     for (int c = tid; c < rows * CPR; c += SH::THREADS) {
         const int r = c / CPR, ch = c % CPR;
         const int col = ct * SH::COLS + ch * (16 / OUT_ES);   // n_out is a multiple of 16 elements: chunks are all in or all out
-        if (col < n_out)
-            *reinterpret_cast<uint4 *>(g.out + (size_t)(tile.row0 + r) * out_pitch + (size_t)col * OUT_ES) =
-                *reinterpret_cast<const uint4 *>(stage_at(r, ch * 16));
+        if (col < n_out) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(stage_at(r, ch * 16));
+            u32x4 *dst = reinterpret_cast<u32x4 *>(g.out + (size_t)(tile.row0 + r) * out_pitch + (size_t)col * OUT_ES);
+            if (g.nt_out) __builtin_nontemporal_store(v, dst);
+            else *dst = v;
+        }
     }
 }
 
@@ -583,6 +587,11 @@ int k_groups_for(int row_bytes)
     return row_bytes % 4096 == 0 ? row_bytes / GM_STEP_BYTES : 1;
 }
 
+// An output that does not fit the L2s (8 x 4 MiB) anyway is written with non-temporal stores:
+// cached stores of such a stream push the token rows the workgroups share out of L2 (measured
+// -4..6 % on the gate/up GEMM); a small output stays cached for the kernel that reads it next.
+int nt_output(size_t bytes) { return bytes > (size_t)32 << 20 ? 1 : 0; }
+
 }  // namespace
 
 int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const void *x,
@@ -591,7 +600,8 @@ int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const 
 {
     GemmArgs g{static_cast<const unsigned char *>(x), x_scale, static_cast<const unsigned char *>(w1), w1_scale,
                sorted_pair, static_cast<unsigned char *>(act), act_scale, c.H, c.I, c.top_k,
-               k_groups_for(c.H * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2))};
+               k_groups_for(c.H * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2)),
+               nt_output((size_t)c.T * c.top_k * c.I * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2))};
     if (c.dtype == MOE_DTYPE_FP8_E4M3) {
         if (c.H > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;  // weight scales of one slab sit in two registers
         return launch_by_tile_rows<true, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
@@ -605,7 +615,8 @@ int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const vo
 {
     GemmArgs g{static_cast<const unsigned char *>(act), act_scale, static_cast<const unsigned char *>(w2), w2_scale,
                nullptr, static_cast<unsigned char *>(y), nullptr, c.I, c.H, c.top_k,
-               k_groups_for(c.I * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2))};
+               k_groups_for(c.I * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2)),
+               nt_output((size_t)c.T * c.top_k * c.H * 2)};
     if (c.dtype == MOE_DTYPE_FP8_E4M3) {
         if (c.I > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;
         return launch_by_tile_rows<false, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
