@@ -17,11 +17,13 @@
  * Parity pins (tests/test_oracle_*.py): brute-force top-k, closed-form softmax
  * over the selected logits, group-routing reductions, permutation identities,
  * dense-MLP special cases against an independent float64 library matmul, the
- * e4m3 decode against a library conversion of all 256 codes, linearity/zero
+ * e4m3 decode against a library conversion of all 256 codes, the 1x128 quantiser
+ * against a library float8 conversion and its own error bound, linearity/zero
  * invariants.  The paper prints no numeric values for this operator, so parity
  * against paper-printed numbers is unpinned; every function is pinned by the
  * above instead.
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -30,6 +32,9 @@
 enum { ORACLE_BF16 = 0, ORACLE_FP8_E4M3 = 1 };
 enum { ORACLE_SOFTMAX = 0, ORACLE_SIGMOID = 1 };
 #define ORACLE_QBLOCK 128
+#if FLT_EVAL_METHOD != 0
+#error "float expressions must be evaluated in binary32 (the quantiser's divisions depend on it)"
+#endif
 
 /* One problem instance: shapes, routing rule, and host pointers to the inputs. */
 typedef struct {
@@ -55,6 +60,13 @@ typedef struct {
      * local_offset -- and the layer output is the sum over a token's chosen experts that
      * fall in that range.  local_count = 0: every expert is local. */
     int32_t local_offset, local_count;
+    /* Quantise-on-the-path mode (the "fp8 packing and scaling" step the paper's kernel table,
+     * Sec. 4.3, names as this operator's challenge, taken into the layer): the layer received
+     * bf16 hidden states x_bf16 [T,H] and quantised them itself with
+     * oracle_quantize_rows_1x128; x / x_scale above hold that result and feed the experts,
+     * while the router scores the hidden states as they arrived.  NULL: x arrived quantised
+     * (or the layer is bf16) and the router reads x. */
+    const uint16_t *x_bf16;
 } oracle_problem;
 
 /* ---- element decoding ---------------------------------------------------- */
@@ -80,6 +92,55 @@ double oracle_e4m3_to_f64(uint8_t b)
     return s ? -v : v;
 }
 
+/* ---- activation quantisation ---------------------------------------------- */
+
+/* Nearest e4m3 code to v (ties -> the code with an even mantissa field), magnitudes beyond the
+ * largest finite value 448 saturate to it.  Written as a search over all 127 non-negative finite
+ * codes so that it rests on oracle_e4m3_to_f64 alone. */
+uint8_t oracle_f32_to_e4m3(float v)
+{
+    const double a = fabs((double)v);
+    int best = 0;
+    double best_d = INFINITY;
+    if (isnan(v)) return 0x7f;
+    for (int c = 0; c <= 0x7e; ++c) {
+        const double d = fabs(oracle_e4m3_to_f64((uint8_t)c) - a);
+        if (d < best_d || (d == best_d && (c & 1) == 0)) { best_d = d; best = c; }
+    }
+    return (uint8_t)(best | (signbit(v) ? 0x80 : 0));
+}
+
+/*
+ * Per-token, per-128-column quantisation of bf16 rows to e4m3 with one fp32 scale per block
+ * (DeepSeek-V3 style 1x128 activation blocks):
+ *   scale[r,b] = amax(|x[r, 128b .. 128b+127]|) / 448        (1 when the block is all zero)
+ *   q[r,c]     = e4m3_nearest_even( x[r,c] / scale[r,c/128] )
+ * The codes are integers decided by floating point, so the precision of the two divisions is
+ * part of the definition: both are IEEE binary32 divisions (bf16 values are exact in binary32;
+ * float expressions are evaluated in binary32 on the SSE targets this file is built for).
+ */
+void oracle_quantize_rows_1x128(int32_t R, int32_t K, const uint16_t *x /* [R,K] bf16 */,
+                                uint8_t *q /* [R,K] */, float *scale /* [R,K/128] */)
+{
+    const int nb = K / ORACLE_QBLOCK;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int r = 0; r < R; ++r)
+        for (int b = 0; b < nb; ++b) {
+            const uint16_t *xb = x + (size_t)r * K + (size_t)b * ORACLE_QBLOCK;
+            float amax = 0.0f;
+            for (int c = 0; c < ORACLE_QBLOCK; ++c) {
+                const float v = fabsf((float)oracle_bf16_to_f64(xb[c]));
+                if (v > amax) amax = v;
+            }
+            const float sc = amax > 0.0f ? amax / 448.0f : 1.0f;
+            scale[(size_t)r * nb + b] = sc;
+            for (int c = 0; c < ORACLE_QBLOCK; ++c) {
+                const float v = (float)oracle_bf16_to_f64(xb[c]) / sc;   /* binary32 quotient */
+                q[(size_t)r * K + (size_t)b * ORACLE_QBLOCK + c] = oracle_f32_to_e4m3(v);
+            }
+        }
+}
+
 static double payload(const void *p, int dtype, size_t idx)
 {
     if (dtype == ORACLE_FP8_E4M3) return oracle_e4m3_to_f64(((const uint8_t *)p)[idx]);
@@ -93,6 +154,14 @@ static double x_at(const oracle_problem *q, int t, int h)
     if (q->dtype == ORACLE_FP8_E4M3)
         v *= (double)q->x_scale[(size_t)t * (q->H / ORACLE_QBLOCK) + h / ORACLE_QBLOCK];
     return v;
+}
+
+/* Hidden state as the router sees it: the bf16 tensor the layer received when it quantises
+ * x itself, else x. */
+static double x_route_at(const oracle_problem *q, int t, int h)
+{
+    if (q->x_bf16) return oracle_bf16_to_f64(q->x_bf16[(size_t)t * q->H + h]);
+    return x_at(q, t, h);
 }
 
 /* Weight W[e,n,c] of an [E,N,K] tensor; fp8: payload times the scale of its
@@ -114,7 +183,7 @@ static void logits_token(const oracle_problem *q, int t, double *z)
     for (int e = 0; e < q->E; ++e) {
         double acc = 0.0;
         for (int h = 0; h < q->H; ++h)
-            acc += x_at(q, t, h) * (double)q->router_w[(size_t)e * q->H + h];
+            acc += x_route_at(q, t, h) * (double)q->router_w[(size_t)e * q->H + h];
         z[e] = acc;
     }
 }

@@ -37,6 +37,7 @@ class _Problem(C.Structure):
         ("x", C.c_void_p), ("x_scale", C.c_void_p), ("router_w", C.c_void_p), ("bias", C.c_void_p),
         ("w1", C.c_void_p), ("w1_scale", C.c_void_p), ("w2", C.c_void_p), ("w2_scale", C.c_void_p),
         ("local_offset", C.c_int32), ("local_count", C.c_int32),
+        ("x_bf16", C.c_void_p),
     ]
 
 
@@ -51,6 +52,8 @@ def lib():
         _lib.oracle_bf16_to_f64.argtypes = [C.c_uint16]
         _lib.oracle_e4m3_to_f64.restype = C.c_double
         _lib.oracle_e4m3_to_f64.argtypes = [C.c_uint8]
+        _lib.oracle_f32_to_e4m3.restype = C.c_uint8
+        _lib.oracle_f32_to_e4m3.argtypes = [C.c_float]
         _lib.oracle_num_threads.restype = C.c_int
     return _lib
 
@@ -103,6 +106,8 @@ class Problem:
     w2_scale: Optional[object] = None
     local_offset: int = 0             # local-expert mode: weights hold experts [offset, offset+count)
     local_count: int = 0              # 0 = all E experts
+    x_bf16: Optional[object] = None   # quantise-on-the-path mode: the bf16 hidden states the layer received
+                                      # (x / x_scale then hold quantize_rows_1x128(x_bf16))
 
     @property
     def EL(self) -> int:
@@ -118,6 +123,9 @@ class Problem:
         self._w1s = _np(self.w1_scale, np.float32)
         self._w2 = _np(self.w2, pay)
         self._w2s = _np(self.w2_scale, np.float32)
+        self._xb = _np(self.x_bf16, np.uint16)
+        if self._xb is not None:
+            assert self.fp8 and self._xb.size == self.T * self.H
         if self._x is not None:
             assert self._x.size == self.T * self.H
         if self._rw is not None:
@@ -135,18 +143,37 @@ class Problem:
             self.topk_group, self.group_score_topn, int(self.fp8), float(self.routed_scale),
             _ptr(self._x), _ptr(self._xs), _ptr(self._rw), _ptr(self._b),
             _ptr(self._w1), _ptr(self._w1s), _ptr(self._w2), _ptr(self._w2s),
-            self.local_offset, self.local_count)
+            self.local_offset, self.local_count, _ptr(self._xb))
 
 
 def problem_from_inputs(inp) -> Problem:
     """Build a Problem from an object with `.wl` (shape/routing fields) and tensors."""
     wl = inp.wl
+    x, x_scale, x_bf16 = inp.x, inp.x_scale, None
+    if getattr(wl, "quantize_x", False):        # the layer quantises its bf16 hidden states itself
+        x_bf16 = inp.x
+        x, x_scale = quantize_rows_1x128(inp.x)
     return Problem(T=wl.T, H=wl.H, I=wl.I, E=wl.E, top_k=wl.top_k, scoring=wl.scoring,
                    renormalize=True, n_group=wl.n_group, topk_group=wl.topk_group,
                    group_score_topn=wl.group_score_topn, routed_scale=wl.routed_scale, fp8=wl.fp8,
-                   x=inp.x, x_scale=inp.x_scale, router_w=inp.router_w, bias=inp.bias,
+                   x=x, x_scale=x_scale, x_bf16=x_bf16, router_w=inp.router_w, bias=inp.bias,
                    w1=inp.w1, w1_scale=inp.w1_scale, w2=inp.w2, w2_scale=inp.w2_scale,
                    local_offset=getattr(wl, "local_offset", 0), local_count=getattr(wl, "local_experts", 0))
+
+
+def quantize_rows_1x128(x_bf16):
+    """bf16 rows [R,K] -> (e4m3 codes [R,K] uint8, scales [R,K/128] float32)."""
+    x = _np(x_bf16, np.uint16)
+    assert x.ndim == 2 and x.shape[1] % 128 == 0
+    R, K = x.shape
+    q = np.empty((R, K), dtype=np.uint8)
+    scale = np.empty((R, K // 128), dtype=np.float32)
+    lib().oracle_quantize_rows_1x128(C.c_int32(R), C.c_int32(K), _ptr(x), _ptr(q), _ptr(scale))
+    return q, scale
+
+
+def f32_to_e4m3(v: float) -> int:
+    return int(lib().oracle_f32_to_e4m3(C.c_float(v)))
 
 
 def _i32(a):

@@ -4,7 +4,8 @@ This module only draws random tensors and stores them in the dtypes the layer
 consumes.  It holds none of the layer's arithmetic: no routing, no GEMM, no
 activation.  The one numeric step here is the block quantisation that turns
 generated values into the fp8 payload + fp32 scales an fp8 workload *arrives*
-with (inputs are quantised before the layer runs, never inside it).
+with.  (Workloads with `quantize_x` hand the layer bf16 hidden states instead and
+the layer quantises them itself; nothing here is used for that.)
 
 Shapes follow the MoE operator the paper analyses (Sec. 4.5: DeepSeek-V3 style,
 256 experts, top-8, hidden size 7168) plus a Mixtral-shaped and a tiny case.
@@ -49,6 +50,7 @@ class Workload:
     hot_bias: float = 0.0
     local_offset: int = 0       # local-expert mode: first expert whose weights are held ...
     local_experts: int = 0      # ... and how many (0 = all E)
+    quantize_x: bool = False    # fp8 only: hidden states arrive as bf16 and the layer quantises them itself
 
     @property
     def EL(self) -> int:
@@ -73,6 +75,11 @@ WORKLOADS: Dict[str, Workload] = {
     # one device's share under 8-way expert parallelism: 32 local experts of 256 (the shape of the
     # paper's Sec. 4.5 workload); experts 96..127 are group 3 of the 8 routing groups
     "fp8_local32": Workload("fp8_local32", T=4096, fp8=True, local_offset=96, local_experts=32, **_DSV3),
+    # fp8 weights, hidden states arriving in bf16: the 1x128 activation quantisation (the "fp8
+    # packing and scaling" the paper's kernel table names for this operator) runs inside the layer
+    "fp8_prefill_qx": Workload("fp8_prefill_qx", T=1024, fp8=True, quantize_x=True, **_DSV3),
+    "fp8_local32_qx": Workload("fp8_local32_qx", T=4096, fp8=True, quantize_x=True, local_offset=96,
+                               local_experts=32, **_DSV3),
 }
 
 # tensor ids for the per-tensor generator streams
@@ -178,7 +185,7 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu",
         hot = hot_expert_ids(wl)
         if hot:
             bias[torch.tensor(hot, device=dev)] += wl.hot_bias
-    if wl.fp8:
+    if wl.fp8 and not wl.quantize_x:
         x, x_scale = quantize_rows_1x128(x32)
     else:
         x, x_scale = x32.to(torch.bfloat16), None

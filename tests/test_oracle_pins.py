@@ -426,3 +426,108 @@ def test_combine_skips_pairs_without_a_row():
     inv_d = inv.copy(); inv_d[dropped] = -1
     w_zero = w.copy().reshape(-1); w_zero[dropped] = 0.0
     np.testing.assert_allclose(orc.combine(w, inv_d, y), orc.combine(w_zero.reshape(T, k), inv, y), rtol=0, atol=0)
+
+
+# ---------------------------------------------------------------- activation quantisation on the path
+
+
+def _lib_e4m3_codes(v32: torch.Tensor) -> np.ndarray:
+    """Library conversion (clamped to the finite range first) -> code bytes."""
+    return v32.clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def test_e4m3_encode_matches_library_cast_including_ties_and_saturation():
+    g = torch.Generator().manual_seed(20)
+    pos = np.array([orc.e4m3_to_f64(c) for c in range(0x7f)])                 # every finite magnitude, ascending
+    mid = (pos[:-1] + pos[1:]) / 2                                              # exact ties (representable in binary32)
+    vals = np.concatenate([pos, mid, np.nextafter(mid.astype(np.float32), np.float32(0)),
+                           np.nextafter(mid.astype(np.float32), np.float32(1e9)),
+                           [448.0, 449.0, 464.0, 1e4, 3e38, 1e-9, 2.0 ** -10, 2.0 ** -9 * 0.999],
+                           (torch.randn(4000, generator=g) * 60).numpy(),
+                           (torch.randn(2000, generator=g) * 0.02).numpy()]).astype(np.float32)
+    vals = np.concatenate([vals, -vals])
+    mine = np.array([orc.f32_to_e4m3(float(v)) for v in vals], dtype=np.uint8)
+    lib = _lib_e4m3_codes(torch.from_numpy(vals))
+    zero = (mine & 0x7f) == 0                                                   # +0 / -0 carry the sign of the input
+    assert np.array_equal(mine & 0x7f, lib & 0x7f)
+    assert np.array_equal(mine[~zero], lib[~zero])
+    # ties go to the even mantissa, beyond 448 saturates, decode(encode(code value)) is the identity
+    assert orc.f32_to_e4m3(float(mid[8])) % 2 == 0 and orc.f32_to_e4m3(1e30) == 0x7e
+    assert all(orc.f32_to_e4m3(float(pos[c])) == c for c in range(0x7f))
+
+
+def test_quantize_rows_matches_library_division_and_cast():
+    g = torch.Generator().manual_seed(21)
+    x = (torch.randn(5, 384, generator=g) * torch.tensor([1e-3, 1.0, 30.0]).repeat_interleave(128)).bfloat16()
+    x[3, 128:256] = 0                                                           # an all-zero block
+    q, s = orc.quantize_rows_1x128(x)
+    b = x.float().reshape(5, 3, 128)
+    amax = b.abs().amax(-1)
+    s_lib = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))          # binary32 division
+    q_lib = _lib_e4m3_codes(b / s_lib[..., None]).reshape(5, 384)
+    assert np.array_equal(s.view(np.uint32), s_lib.numpy().view(np.uint32))
+    zero = (q & 0x7f) == 0
+    assert np.array_equal(q & 0x7f, q_lib & 0x7f) and np.array_equal(q[~zero], q_lib[~zero])
+    assert (s[3, 1] == 1.0) and (q[3, 128:256] & 0x7f == 0).all()
+    # every block's largest magnitude lands on the largest code, with its sign
+    xf = x.float().numpy().reshape(5, 3, 128)
+    qb = q.reshape(5, 3, 128)
+    for r in range(5):
+        for blk in range(3):
+            if (r, blk) == (3, 1):
+                continue
+            j = int(np.abs(xf[r, blk]).argmax())
+            assert qb[r, blk, j] == (0x7e | (0x80 if xf[r, blk, j] < 0 else 0))
+
+
+def test_quantize_rows_is_exact_on_representable_blocks_and_bounded_elsewhere():
+    g = torch.Generator().manual_seed(22)
+    codes = torch.randint(0, 0x7f, (4, 256), generator=g).to(torch.uint8)
+    codes[:, 7] = 0x7e
+    codes[:, 128 + 9] = 0x7e                                                    # amax of each block = 448 * 2^-5
+    sign = torch.randint(0, 2, (4, 256), generator=g).to(torch.uint8) << 7
+    val = (codes | sign).view(torch.float8_e4m3fn).float() * 2.0 ** -5          # exact in bf16 (4 significant bits)
+    q, s = orc.quantize_rows_1x128(val.bfloat16())
+    assert (s == 2.0 ** -5).all()
+    deq = np.array([orc.e4m3_to_f64(int(c)) for c in q.reshape(-1)]).reshape(4, 256) * 2.0 ** -5
+    assert np.array_equal(deq, val.double().numpy())
+    # generic values: relative error of one e4m3 rounding, plus half a subnormal step near zero
+    x = (torch.randn(6, 512, generator=g) * 3).bfloat16()
+    q, s = orc.quantize_rows_1x128(x)
+    deq = np.array([orc.e4m3_to_f64(int(c)) for c in q.reshape(-1)]).reshape(6, 512) * np.repeat(s.astype(np.float64), 128, axis=1)
+    xv = x.double().numpy()
+    assert (np.abs(deq - xv) <= np.abs(xv) * 2.0 ** -4 + np.repeat(s, 128, axis=1) * 2.0 ** -10).all()
+    # negating the input flips exactly the sign bits
+    qn, sn = orc.quantize_rows_1x128(-x)
+    assert np.array_equal(sn, s) and np.array_equal(qn ^ 0x80, q)
+
+
+def test_quantize_on_the_path_routes_on_bf16_and_feeds_quantised_rows_to_the_experts():
+    wl = _wl(T=6, H=256, I=128, E=4, top_k=2, fp8=True, quantize_x=True, scoring="sigmoid")
+    inp = syn.make_inputs(wl, seed=23)
+    assert inp.x.dtype == torch.bfloat16 and inp.x_scale is None
+    p = orc.problem_from_inputs(inp)
+    out, ids, w, _ = orc.forward(p)
+    # router: float64 library matmul of the bf16 hidden states as they arrived
+    z = orc.router_logits(p)
+    np.testing.assert_allclose(z, _f64(inp.x) @ _f64(inp.router_w).T, rtol=1e-12, atol=1e-13)
+    ids2, w2, _ = orc.route(p, z)
+    assert np.array_equal(ids, ids2) and np.array_equal(w, w2)
+    # experts: dense MLP on the dequantised library quantisation of x
+    b = inp.x.float().reshape(wl.T, 2, 128)
+    sc = b.abs().amax(-1) / 448.0
+    xq = (b / sc[..., None]).clamp(-448, 448).to(torch.float8_e4m3fn).double() * sc[..., None].double()
+    xq = xq.reshape(wl.T, wl.H).numpy()
+    ref = np.zeros_like(out)
+    for t in range(wl.T):
+        for j in range(wl.top_k):
+            e = int(ids[t, j])
+            w1 = _f64(inp.w1[e]) * np.kron(_f64(inp.w1_scale[e]), np.ones((128, 128)))
+            w2m = _f64(inp.w2[e]) * np.kron(_f64(inp.w2_scale[e]), np.ones((128, 128)))
+            ref[t] += w[t, j] * _dense_mlp(xq[t:t + 1], w1, w2m, wl.I)[0]
+    np.testing.assert_allclose(out, ref, rtol=1e-11, atol=1e-13)
+    # and it differs from routing on the quantised hidden states only through the logits
+    p_q = orc.Problem(**{**{f: getattr(p, f) for f in ("T", "H", "I", "E", "top_k", "scoring", "renormalize", "n_group",
+                                                        "topk_group", "group_score_topn", "routed_scale", "fp8", "x",
+                                                        "x_scale", "router_w", "bias", "w1", "w1_scale", "w2", "w2_scale")}})
+    assert not np.array_equal(orc.router_logits(p_q), z)
