@@ -148,7 +148,8 @@ def main():
     bw = 1 if wl.fp8 else 2                      # bytes per weight / activation payload element
     scale_w = (e_active * (2 * I // 128) * (H // 128) + e_active * (H // 128) * (I // 128)) * 4 if wl.fp8 else 0
     flops = 6.0 * H * I * P + 2.0 * T * E * H
-    bytes_min = e_active * 3 * H * I * bw + scale_w + T * H * bw + E * H * 4 + T * H * 2
+    bx = 2 if wl.quantize_x else bw           # hidden states arrive as bf16 when the layer quantises them itself
+    bytes_min = e_active * 3 * H * I * bw + scale_w + T * H * bx + E * H * 4 + T * H * 2
     sec = ms_per_step * 1e-3
     kind = "fp8" if wl.fp8 else "bf16"
     tflops = flops / sec / 1e12

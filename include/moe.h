@@ -32,6 +32,11 @@
  *     here.  Pairs routed elsewhere are dropped by the sort-scatter and contribute
  *     nothing to `out`, which is then this device's partial sum of the layer.
  *     EL below is num_local_experts, or E when that field is 0.
+ *   - Quantise-on-the-path mode (cfg->quantize_x = 1, fp8 layers): the hidden states
+ *     arrive as bf16 and the per-token 1x128 block quantisation that an fp8 expert GEMM
+ *     needs (the "fp8 packing and scaling" that the paper's kernel table in Sec. 4.3
+ *     names as this operator's difficulty) is a step of the layer instead of the
+ *     caller's job.
  */
 #ifndef MOE_H
 #define MOE_H
@@ -70,6 +75,10 @@ typedef struct moe_config {
     float   routed_scale;       /* final factor on the k weights */
     int32_t local_expert_offset;/* first expert whose weights this call holds */
     int32_t num_local_experts;  /* how many it holds; 0 = all E (then the offset must be 0) */
+    int32_t quantize_x;         /* 1 (dtype fp8 only): x arrives as bf16 and the layer quantises it
+                                   to e4m3 per 1x128 block itself (moe_quantize_act); the router
+                                   scores the bf16 values.  Only moe_forward, moe_route and the
+                                   size queries look at this field */
 } moe_config;
 
 /* Row count of one tile of the grouped GEMMs for this problem (the height the
@@ -93,7 +102,8 @@ size_t moe_workspace_size(const moe_config *cfg);
  * Routing (paper Sec. 4.5 "Routing": score all experts per token, keep the top-k).
  * Logits z[t,e] = sum_h x[t,h] * router_w[e,h] in fp32, then the scoring rule of
  * cfg; one wavefront per token selects the k experts with cross-lane exchanges.
- *   x         [T,H] bf16, or fp8 e4m3 with x_scale [T,H/128] fp32 (else x_scale NULL)
+ *   x         [T,H] bf16, or fp8 e4m3 with x_scale [T,H/128] fp32 (else x_scale NULL);
+ *             with cfg->quantize_x the router is handed the bf16 tensor whatever cfg->dtype says
  *   router_w  [E,H] fp32;  bias [E] fp32 or NULL (added to the choice key only)
  *   ids_out   [T,k] int32, experts in descending key order, equal keys -> lower index
  *   w_out     [T,k] fp32, w = s[id] (/ sum over the k if renormalize) * routed_scale
@@ -103,6 +113,17 @@ size_t moe_workspace_size(const moe_config *cfg);
 int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
               const float *bias, int32_t *ids_out, float *w_out,
               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Activation quantisation for the fp8 expert GEMMs (paper Sec. 4.3, kernel table: the fp8
+ * MoE operator's "packing and scaling"; DeepSeek-V3 style 1x128 activation blocks):
+ *   scale[t,b] = max |x[t, 128b .. 128b+127]| / 448      (1 when the block is all zero)
+ *   q[t,c]     = e4m3( x[t,c] / scale[t,c/128] )         round to nearest even, |.| <= 448
+ * with both divisions in IEEE binary32, so the result is the same bits on every run and machine.
+ *   x [T,H] bf16 -> xq_out [T,H] fp8 e4m3 (OCP e4m3fn), x_scale_out [T,H/128] fp32; H % 128 == 0.
+ * cfg->dtype and cfg->quantize_x are not consulted; T and H are.
+ */
+int moe_quantize_act(const moe_config *cfg, const void *x, void *xq_out, float *x_scale_out, void *stream);
 
 /*
  * Sort-scatter (paper Sec. 4.5: reorder tokens by expert into contiguous memory).
@@ -159,6 +180,9 @@ int moe_combine(const moe_config *cfg, const void *y, const float *w, const int3
  * The whole layer: the five steps above enqueued back to back on `stream`,
  * intermediates in `workspace` (>= moe_workspace_size(cfg) bytes, 256-byte aligned).
  * bias / *_scale may be NULL as described per step.  out [T,H] bf16.
+ * With cfg->quantize_x, x is [T,H] bf16 and x_scale is ignored: moe_quantize_act runs first
+ * (its outputs live in the workspace), the router reads the bf16 x, the gate/up GEMM the
+ * quantised copy.
  */
 int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
                 const float *bias, const void *w1, const float *w1_scale, const void *w2,
@@ -169,7 +193,8 @@ int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, cons
  * moe_forward with step boundaries marked for timing: `events` is a HOST array of
  * MOE_FORWARD_EVENTS hipEvent_t handles (created by the caller) that are recorded
  * on `stream` before routing and after each of the five steps, in pipeline order
- * (route, sort-scatter, gate/up GEMM, down GEMM, combine).  The kernels and their
+ * (route, sort-scatter, gate/up GEMM, down GEMM, combine; with cfg->quantize_x the
+ * quantisation of x is inside the first interval).  The kernels and their
  * launch configuration are exactly those of moe_forward.
  */
 enum { MOE_FORWARD_EVENTS = 6 };

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libmoe_gfx950.so")
 
 EXPORTS = [
     "moe_tile_rows", "moe_max_tiles", "moe_route_workspace_size", "moe_workspace_size",
-    "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm_down",
+    "moe_route", "moe_quantize_act", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm_down",
     "moe_combine", "moe_forward", "moe_forward_marked", "moe_error_string", "moe_last_hip_error",
 ]
 
@@ -36,13 +36,15 @@ class MoEConfig(C.Structure):
         ("topk_group", C.c_int32), ("group_score_topn", C.c_int32), ("dtype", C.c_int32),
         ("routed_scale", C.c_float),
         ("local_expert_offset", C.c_int32), ("num_local_experts", C.c_int32),
+        ("quantize_x", C.c_int32),
     ]
 
     @classmethod
     def from_workload(cls, wl) -> "MoEConfig":
         return cls(wl.T, wl.H, wl.I, wl.E, wl.top_k, {"softmax": 0, "sigmoid": 1}[wl.scoring], 1,
                    wl.n_group, wl.topk_group, wl.group_score_topn, 1 if wl.fp8 else 0,
-                   float(wl.routed_scale), wl.local_offset, wl.local_experts)
+                   float(wl.routed_scale), wl.local_offset, wl.local_experts,
+                   1 if getattr(wl, "quantize_x", False) else 0)
 
     @property
     def P(self) -> int:
@@ -76,6 +78,8 @@ def load():
     lib.moe_workspace_size.argtypes = [cfgp]
     lib.moe_route.restype = C.c_int
     lib.moe_route.argtypes = [cfgp, vp, f32p, f32p, f32p, i32p, f32p, vp, C.c_size_t, vp]
+    lib.moe_quantize_act.restype = C.c_int
+    lib.moe_quantize_act.argtypes = [cfgp, vp, vp, f32p, vp]
     lib.moe_permute.restype = C.c_int
     lib.moe_permute.argtypes = [cfgp, i32p, i32p, i32p, i32p, vp, i32p, vp]
     lib.moe_grouped_gemm_swiglu.restype = C.c_int
@@ -120,6 +124,11 @@ def _payload(cfg: MoEConfig):
     return torch.float8_e4m3fn if cfg.dtype == 1 else torch.bfloat16
 
 
+def _x_arrives_as(cfg: MoEConfig):
+    """dtype of the hidden states handed to moe_route / moe_forward (bf16 when the layer quantises them itself)."""
+    return torch.bfloat16 if cfg.quantize_x else _payload(cfg)
+
+
 def _expect(t, shape, dtype, name):
     if t is None:
         return
@@ -153,7 +162,7 @@ def _bytes(n: int, device) -> torch.Tensor:
 
 def moe_route(cfg, x, x_scale, router_w, bias, ids_out=None, w_out=None, workspace=None):
     dev = x.device
-    _expect(x, (cfg.T, cfg.H), _payload(cfg), "x")
+    _expect(x, (cfg.T, cfg.H), _x_arrives_as(cfg), "x")
     _expect(router_w, (cfg.E, cfg.H), torch.float32, "router_w")
     _expect(bias, (cfg.E,), torch.float32, "bias")
     _expect(x_scale, (cfg.T, cfg.H // 128), torch.float32, "x_scale")
@@ -164,6 +173,16 @@ def moe_route(cfg, x, x_scale, router_w, bias, ids_out=None, w_out=None, workspa
                           _p(workspace), C.c_size_t(workspace.numel()), _stream())
     _check(rc, "moe_route")
     return ids_out, w_out
+
+
+def moe_quantize_act(cfg, x):
+    """bf16 [T,H] -> (e4m3 payload [T,H], fp32 scales [T,H/128])."""
+    _expect(x, (cfg.T, cfg.H), torch.bfloat16, "x")
+    xq = torch.empty((cfg.T, cfg.H), dtype=torch.float8_e4m3fn, device=x.device)
+    xs = torch.empty((cfg.T, cfg.H // 128), dtype=torch.float32, device=x.device)
+    rc = load().moe_quantize_act(C.byref(cfg), _p(x), _p(xq), _p(xs), _stream())
+    _check(rc, "moe_quantize_act")
+    return xq, xs
 
 
 def moe_permute(cfg, ids):
@@ -221,7 +240,7 @@ def moe_forward(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out
                 events=None):
     """`events`: optional ctypes array of FORWARD_EVENTS hipEvent_t handles (see moe_forward_marked)."""
     dev = x.device
-    _expect(x, (cfg.T, cfg.H), _payload(cfg), "x")
+    _expect(x, (cfg.T, cfg.H), _x_arrives_as(cfg), "x")
     _expect(router_w, (cfg.E, cfg.H), torch.float32, "router_w")
     _expect(w1, (cfg.EL, 2 * cfg.I, cfg.H), _payload(cfg), "w1")
     _expect(w2, (cfg.EL, cfg.H, cfg.I), _payload(cfg), "w2")

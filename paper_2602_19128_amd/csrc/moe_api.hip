@@ -27,6 +27,8 @@ int validate(const moe_config *c)
     if (c->local_expert_offset < 0 || c->num_local_experts < 0) return MOE_ERR_INVALID;
     if (c->num_local_experts == 0 && c->local_expert_offset != 0) return MOE_ERR_INVALID;
     if (c->local_expert_offset + c->num_local_experts > c->E) return MOE_ERR_INVALID;
+    if (c->quantize_x != 0 && c->quantize_x != 1) return MOE_ERR_INVALID;
+    if (c->quantize_x == 1 && c->dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_INVALID;
     if (c->n_group > 1) {
         if (c->E % c->n_group != 0) return MOE_ERR_INVALID;
         const int gsz = c->E / c->n_group;
@@ -60,8 +62,17 @@ int max_tiles_for(const moe_config &c)
 
 // Workspace sections of moe_forward, in order, each 256-byte aligned.
 struct Layout {
-    size_t route, ids, w, offsets, sorted_pair, inv, tiles, ntiles, act, act_scale, y, total;
+    size_t route, ids, w, offsets, sorted_pair, inv, tiles, ntiles, act, act_scale, y, xq, xq_scale, total;
 };
+
+// The problem as the router sees it: with quantise-on-the-path the router scores the bf16 hidden
+// states the layer received, not the fp8 copy made for the experts.
+moe_config router_view(const moe_config &c)
+{
+    moe_config r = c;
+    if (c.quantize_x) r.dtype = MOE_DTYPE_BF16;
+    return r;
+}
 
 Layout layout_for(const moe_config &c)
 {
@@ -70,7 +81,7 @@ Layout layout_for(const moe_config &c)
     Layout l;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t at = off; off += align_up(bytes ? bytes : 1, 256); return at; };
-    l.route = take(route_workspace_bytes(c));
+    l.route = take(route_workspace_bytes(router_view(c)));
     l.ids = take(P * sizeof(int32_t));
     l.w = take(P * sizeof(float));
     l.offsets = take(((size_t)local_experts(c) + 1) * sizeof(int32_t));
@@ -81,6 +92,8 @@ Layout layout_for(const moe_config &c)
     l.act = take(P * c.I * act_elem);
     l.act_scale = take(c.dtype == MOE_DTYPE_FP8_E4M3 ? P * (c.I / kQBlock) * sizeof(float) : 0);
     l.y = take(P * c.H * 2);
+    l.xq = take(c.quantize_x ? (size_t)c.T * c.H : 0);
+    l.xq_scale = take(c.quantize_x ? (size_t)c.T * (c.H / kQBlock) * sizeof(float) : 0);
     l.total = off;
     return l;
 }
@@ -99,7 +112,7 @@ int32_t moe_max_tiles(const moe_config *cfg) { return validate(cfg) == MOE_OK ? 
 
 size_t moe_route_workspace_size(const moe_config *cfg)
 {
-    return validate(cfg) == MOE_OK ? route_workspace_bytes(*cfg) : 0;
+    return validate(cfg) == MOE_OK ? route_workspace_bytes(router_view(*cfg)) : 0;
 }
 
 size_t moe_workspace_size(const moe_config *cfg) { return validate(cfg) == MOE_OK ? layout_for(*cfg).total : 0; }
@@ -112,9 +125,21 @@ int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const 
     if (rc != MOE_OK) return rc;
     if (cfg->T == 0) return MOE_OK;
     if (!x || !router_w || !ids_out || !w_out || !workspace) return MOE_ERR_INVALID;
-    if (fp8(cfg) && !x_scale) return MOE_ERR_INVALID;
-    if (workspace_bytes < route_workspace_bytes(*cfg)) return MOE_ERR_WORKSPACE;
-    return launch_route(*cfg, x, x_scale, router_w, bias, ids_out, w_out, workspace, (hipStream_t)stream);
+    const moe_config rv = router_view(*cfg);
+    if (fp8(&rv) && !x_scale) return MOE_ERR_INVALID;
+    if (workspace_bytes < route_workspace_bytes(rv)) return MOE_ERR_WORKSPACE;
+    return launch_route(rv, x, fp8(&rv) ? x_scale : nullptr, router_w, bias, ids_out, w_out, workspace,
+                        (hipStream_t)stream);
+}
+
+int moe_quantize_act(const moe_config *cfg, const void *x, void *xq_out, float *x_scale_out, void *stream)
+{
+    if (cfg == nullptr || cfg->T < 0 || cfg->H <= 0) return MOE_ERR_INVALID;
+    if (cfg->H % kQBlock != 0) return MOE_ERR_UNSUPPORTED;
+    if ((long long)cfg->T * cfg->H > (1ll << 40)) return MOE_ERR_UNSUPPORTED;
+    if (cfg->T == 0) return MOE_OK;
+    if (!x || !xq_out || !x_scale_out) return MOE_ERR_INVALID;
+    return launch_quantize_act(*cfg, x, xq_out, x_scale_out, (hipStream_t)stream);
 }
 
 int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out, int32_t *sorted_pair_out,
@@ -173,7 +198,7 @@ int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scal
     if (rc != MOE_OK) return rc;
     if (cfg->T == 0) return MOE_OK;
     if (!x || !router_w || !w1 || !w2 || !out || !workspace) return MOE_ERR_INVALID;
-    if (fp8(cfg) && (!x_scale || !w1_scale || !w2_scale)) return MOE_ERR_INVALID;
+    if (fp8(cfg) && ((!x_scale && !cfg->quantize_x) || !w1_scale || !w2_scale)) return MOE_ERR_INVALID;
     if (((uintptr_t)workspace & 255u) != 0) return MOE_ERR_INVALID;
     const Layout l = layout_for(*cfg);
     if (workspace_bytes < l.total) return MOE_ERR_WORKSPACE;
@@ -200,7 +225,18 @@ int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scal
     };
 
     if ((rc = mark()) != MOE_OK) return rc;
-    rc = launch_route(*cfg, x, x_scale, router_w, bias, ids, w, ws + l.route, s);
+    const void *x_route = x;                                  // what the router scores
+    const float *x_route_scale = x_scale;
+    if (cfg->quantize_x) {
+        // bf16 hidden states in: the experts read the e4m3 copy made here, the router the original
+        float *xq_scale = reinterpret_cast<float *>(ws + l.xq_scale);
+        rc = launch_quantize_act(*cfg, x, ws + l.xq, xq_scale, s);
+        if (rc != MOE_OK) return rc;
+        x = ws + l.xq;
+        x_scale = xq_scale;
+        x_route_scale = nullptr;
+    }
+    rc = launch_route(router_view(*cfg), x_route, x_route_scale, router_w, bias, ids, w, ws + l.route, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
     rc = launch_permute(*cfg, tr, mt, ids, offsets, sorted_pair, inv, tiles, ntiles, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;

@@ -49,6 +49,7 @@ inline int check_launch()
 size_t route_workspace_bytes(const moe_config &c);
 int launch_route(const moe_config &c, const void *x, const float *x_scale, const float *router_w,
                  const float *bias, int32_t *ids, float *w, void *ws, hipStream_t s);
+int launch_quantize_act(const moe_config &c, const void *x, void *xq, float *x_scale, hipStream_t s);
 int launch_permute(const moe_config &c, int tile_rows, int max_tiles, const int32_t *ids,
                    int32_t *offsets, int32_t *sorted_pair, int32_t *inv, moe_tile *tiles,
                    int32_t *ntiles, hipStream_t s);

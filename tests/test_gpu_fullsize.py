@@ -99,7 +99,29 @@ def test_fp8_prefill_full_size():
     _check_workload(gpu, gpu.to("cpu"))
 
 
-def test_fp8_local_experts_full_size():
-    """One device's share of the DeepSeek-V3-shaped layer: 32 local experts of 256."""
+@pytest.fixture(scope="module")
+def local32():
     gpu = syn.make_inputs(syn.WORKLOADS["fp8_local32"], seed=0, device="cuda")
-    _check_workload(gpu, gpu.to("cpu"))
+    return gpu, gpu.to("cpu")
+
+
+def test_fp8_local_experts_full_size(local32):
+    """One device's share of the DeepSeek-V3-shaped layer: 32 local experts of 256."""
+    _check_workload(*local32)
+
+
+def test_fp8_local_experts_quantise_on_the_path_full_size(local32):
+    """The same share fed bf16 hidden states: the layer quantises them itself (1x128 blocks), the
+    router scores the bf16 values.  The quantiser is also compared bit for bit on sampled rows."""
+    base, host_w = local32
+    wl = syn.WORKLOADS["fp8_local32_qx"]
+    gpu = syn.make_inputs(wl, seed=0, device="cuda", weights_from=base)
+    assert gpu.x.dtype == torch.bfloat16 and gpu.x_scale is None
+    cfg = moe.MoEConfig.from_workload(wl)
+    xq, xs = moe.moe_quantize_act(cfg, gpu.x)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(1).choice(wl.T, size=96, replace=False))
+    q_ref, s_ref = orc.quantize_rows_1x128(gpu.x[torch.from_numpy(rows).cuda()].cpu())
+    assert np.array_equal(xs.cpu().numpy()[rows].view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(xq.cpu().view(torch.uint8).numpy()[rows], q_ref)
+    _check_workload(gpu, host_w)

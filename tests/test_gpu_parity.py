@@ -43,6 +43,10 @@ CASES = {
     "many_tokens": syn.Workload("many_tokens", T=600, H=256, I=64, E=40, top_k=4),
     "many_tokens_fp8": syn.Workload("many_tokens_fp8", T=530, H=384, I=128, E=64, top_k=6, n_group=4, topk_group=3,
                                     fp8=True, **GROUPED),
+    # fp8 layers that receive bf16 hidden states and quantise them on the path (1x128 blocks)
+    "qx_small": syn.Workload("qx_small", T=150, H=256, I=256, E=8, top_k=2, fp8=True, quantize_x=True),
+    "qx_grouped_local": syn.Workload("qx_grouped_local", T=530, H=384, I=128, E=64, top_k=6, n_group=4, topk_group=3,
+                                     fp8=True, quantize_x=True, local_offset=16, local_experts=32, **GROUPED),
     # the limits of the interface: 512 experts (8 per lane in the router) and 64 experts per token
     "max_experts": syn.Workload("max_experts", T=40, H=128, I=64, E=512, top_k=64),
 }
@@ -90,6 +94,15 @@ def _staged(case):
     return wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv
 
 
+def _gemm_x(gpu, p):
+    """Hidden states as the gate/up GEMM reads them.  When the layer quantises bf16 input itself the
+    staged GEMM is fed the oracle's quantisation (the GPU's own is checked in test_quantize_act)."""
+    if not gpu.wl.quantize_x:
+        return gpu.x, gpu.x_scale
+    xq = torch.from_numpy(p._x.reshape(gpu.wl.T, gpu.wl.H)).view(torch.float8_e4m3fn).cuda()
+    return xq, torch.from_numpy(p._xs.reshape(gpu.wl.T, -1)).cuda()
+
+
 def _act_f64(act, scale):
     """Activations as the GPU stored them (bf16, or fp8 payload x 1x128 scale) in float64."""
     a = f64(act)
@@ -100,7 +113,7 @@ def _act_f64(act, scale):
 
 def test_gemm_swiglu(case):
     wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
-    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
+    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, *_gemm_x(gpu, p), gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
     torch.cuda.synchronize()
     ref = orc.swiglu_rows(p, tok, exp)
     n = len(tok)                                             # rows beyond the kept pairs are never written
@@ -120,7 +133,7 @@ def test_gemm_swiglu(case):
 
 def test_gemm_down(case):
     wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
-    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
+    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, *_gemm_x(gpu, p), gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
     y_g = moe.moe_grouped_gemm_down(cfg, act_g, sc_g, gpu.w2, gpu.w2_scale, tiles, ntiles)
     torch.cuda.synchronize()
     n = len(tok)
@@ -163,6 +176,25 @@ def test_forward(case):
     max_rel, mean_rel = err_stats(got[same_set], ref[same_set])
     print(f"forward {wl.name}: max_rel={max_rel:.2e} mean_rel={mean_rel:.2e} tie-excused tokens={other}")
     assert max_rel <= TOL_MAX[wl.fp8] and mean_rel <= TOL_MEAN[wl.fp8]
+
+
+@pytest.mark.parametrize("T, H, scale", [(1, 128, 1.0), (37, 384, 30.0), (300, 7168, 1.0), (64, 2048, 1e-3)])
+def test_quantize_act_is_bit_exact(T, H, scale):
+    """The 1x128 activation quantiser against the oracle: same code bytes, same scale bits."""
+    g = torch.Generator().manual_seed(T * 1000 + H)
+    x = (torch.randn((T, H), generator=g) * scale).bfloat16()
+    x[0, :128] = 0                                           # an all-zero block (scale 1, codes 0)
+    if T > 1:
+        x[1, :128] = x[1, :128].abs()                        # a block without negative values
+        x[T - 1, H - 128:] = torch.arange(128).bfloat16() * -0.25    # exact small multiples, largest last
+        x[T // 2, 5] = -0.0
+    cfg = moe.MoEConfig(T=T, H=H, I=128, E=8, top_k=2, dtype=1)
+    print(f"\n[quantize] T={T} H={H} scale={scale}", flush=True)
+    xq, xs = moe.moe_quantize_act(cfg, x.cuda())
+    torch.cuda.synchronize()
+    q_ref, s_ref = orc.quantize_rows_1x128(x)
+    assert np.array_equal(xs.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(xq.cpu().view(torch.uint8).numpy(), q_ref)
 
 
 def test_forward_zero_tokens_and_errors():

@@ -74,6 +74,8 @@ def test_size_queries_and_tile_heights(lib):
     (dict(local_expert_offset=4, num_local_experts=5), -1),             # local range past the last expert
     (dict(local_expert_offset=2, num_local_experts=0), -1),             # offset without a local count
     (dict(num_local_experts=-1), -1),
+    (dict(quantize_x=1), -1),                                           # quantise-on-the-path needs an fp8 layer
+    (dict(quantize_x=2, dtype=1), -1),
 ])
 def test_bad_problem_statements_are_refused(lib, change, code):
     cfg = moe.MoEConfig(T=16, H=256, I=128, E=8, top_k=2, scoring=0, renormalize=1, n_group=1,
@@ -100,6 +102,31 @@ def test_null_pointers_and_small_workspace_are_refused(lib):
     assert rc == -1                      # workspace not 256-byte aligned
     assert lib.moe_error_string(-3) == b"workspace too small"
     assert lib.moe_forward(None, one, None, one, None, one, None, one, None, one, one, C.c_size_t(0), None) == -1
+
+
+def test_quantise_on_the_path_sizes_and_argument_checks(lib):
+    wl = syn.WORKLOADS["fp8_prefill"]
+    cfg = moe.MoEConfig.from_workload(wl)
+    cfg_q = moe.MoEConfig.from_workload(syn.WORKLOADS["fp8_prefill_qx"])
+    assert cfg_q.quantize_x == 1 and cfg.quantize_x == 0
+    # the workspace grows by the e4m3 copy of x and its scales
+    extra = moe.moe_workspace_size(cfg_q) - moe.moe_workspace_size(cfg)
+    assert wl.T * wl.H + wl.T * (wl.H // 128) * 4 <= extra <= wl.T * wl.H + wl.T * (wl.H // 128) * 4 + wl.T * wl.E * 64
+    one = C.c_void_p(256)
+    # x_scale may be missing when the layer makes it itself, the weight scales may not
+    big = C.c_size_t(1 << 40)
+    assert lib.moe_forward(C.byref(cfg), one, None, one, None, one, one, one, one, one, one, big, None) == -1
+    assert lib.moe_forward(C.byref(cfg_q), one, None, one, None, one, None, one, one, one, one, big, None) == -1
+    assert lib.moe_forward(C.byref(cfg_q), one, None, one, None, one, one, one, one, one, one, C.c_size_t(16), None) == -3
+    # moe_quantize_act: H must be a multiple of 128, pointers present; zero tokens is a no-op
+    bad = moe.MoEConfig(T=4, H=192, I=128, E=8, top_k=2, dtype=1)
+    assert lib.moe_quantize_act(C.byref(bad), one, one, one, None) == -2
+    ok = moe.MoEConfig(T=4, H=256, I=128, E=8, top_k=2, dtype=1)
+    assert lib.moe_quantize_act(C.byref(ok), None, one, one, None) == -1
+    assert lib.moe_quantize_act(C.byref(ok), one, one, None, None) == -1
+    none = moe.MoEConfig(T=0, H=256, I=128, E=8, top_k=2, dtype=1)
+    assert lib.moe_quantize_act(C.byref(none), None, None, None, None) == 0
+    assert lib.moe_quantize_act(None, one, one, one, None) == -1
 
 
 def test_binding_refuses_cpu_tensors(lib):
