@@ -89,10 +89,21 @@ int32_t moe_max_tiles(const moe_config *cfg);
 
 /* One tile-list record: rows [row0, row0+rows) of the expert-sorted order all
  * belong to `expert`; `first` is the index of that expert's first record and
- * `count` how many records the expert has. */
+ * `count` how many records the expert has (they are consecutive). */
 typedef struct moe_tile {
     int32_t expert, row0, rows, first, count, pad0, pad1, pad2;
 } moe_tile;
+
+/* The tile list doubles as the schedule of the grouped GEMMs.  It is cut into
+ * MOE_WORK_RANGES consecutive ranges (one per XCD of the device); moe_permute
+ * describes them in an int32 array of MOE_SCHED_INTS entries:
+ *   sched[0]      records written
+ *   sched[1 + r]  index of the first record of range r, r = 0..MOE_WORK_RANGES
+ *                 (the last entry is the end: equal to sched[0])
+ * Experts are ranked by their row count, largest first (equal counts: lower index
+ * first), and dealt to the ranges in snake order (0..7, 7..0, ...), so every range
+ * lists its tallest tiles first and the ranges carry similar loads. */
+enum { MOE_WORK_RANGES = 8, MOE_SCHED_INTS = 16 };
 
 /* Bytes of device scratch moe_route / moe_forward need for this problem. */
 size_t moe_route_workspace_size(const moe_config *cfg);
@@ -135,13 +146,14 @@ int moe_quantize_act(const moe_config *cfg, const void *x, void *xq_out, float *
  *   inv_out      [P] int32, sorted row of each pair (-1 for a dropped pair)
  *   tiles_out    [moe_max_tiles(cfg)] records of at most moe_tile_rows(cfg) rows (an expert with
  *                more rows is cut into the fewest such tiles, of equal height rounded up to
- *                16 rows), experts in ascending order, none for an expert without tokens
+ *                16 rows), in schedule order (see moe_tile), none for an expert without tokens
  *                (such experts cost nothing downstream); `expert` counts from the first local expert (it
- *                indexes w1 / w2); ntiles_out [1] int32 = records written
+ *                indexes w1 / w2)
+ *   sched_out    [MOE_SCHED_INTS] int32: records written and the work ranges (see moe_tile)
  */
 int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
                 int32_t *sorted_pair_out, int32_t *inv_out, moe_tile *tiles_out,
-                int32_t *ntiles_out, void *stream);
+                int32_t *sched_out, void *stream);
 
 /*
  * Gate/up grouped GEMM with fused SiLU gating (paper Sec. 4.5: "up" and "gate"
@@ -155,7 +167,7 @@ int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
  */
 int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x_scale,
                             const void *w1, const float *w1_scale, const int32_t *sorted_pair,
-                            const moe_tile *tiles, const int32_t *ntiles,
+                            const moe_tile *tiles, const int32_t *sched,
                             void *act_out, float *act_scale_out, void *stream);
 
 /*
@@ -165,7 +177,7 @@ int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x
  */
 int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *act_scale,
                           const void *w2, const float *w2_scale, const moe_tile *tiles,
-                          const int32_t *ntiles, void *y_out, void *stream);
+                          const int32_t *sched, void *y_out, void *stream);
 
 /*
  * Weighted combine: out[t,:] = sum_{j<k} w[t,j] * y[inv[t*k+j],:], summed in slot

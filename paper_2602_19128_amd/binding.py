@@ -22,6 +22,8 @@ EXPORTS = [
 ]
 
 TILE_INTS = 8            # int32 fields of one moe_tile record
+SCHED_INTS = 16          # int32 entries of the schedule header moe_permute writes (MOE_SCHED_INTS)
+WORK_RANGES = 8          # MOE_WORK_RANGES
 
 
 class MoEError(RuntimeError):
@@ -193,32 +195,32 @@ def moe_permute(cfg, ids):
     sorted_pair = torch.empty((max(P, 1),), dtype=torch.int32, device=dev)
     inv = torch.empty((max(P, 1),), dtype=torch.int32, device=dev)
     tiles = torch.zeros((max(moe_max_tiles(cfg), 1), TILE_INTS), dtype=torch.int32, device=dev)
-    ntiles = torch.zeros((1,), dtype=torch.int32, device=dev)
-    rc = load().moe_permute(C.byref(cfg), _p(ids), _p(offsets), _p(sorted_pair), _p(inv), _p(tiles), _p(ntiles),
+    sched = torch.zeros((SCHED_INTS,), dtype=torch.int32, device=dev)
+    rc = load().moe_permute(C.byref(cfg), _p(ids), _p(offsets), _p(sorted_pair), _p(inv), _p(tiles), _p(sched),
                             _stream())
     _check(rc, "moe_permute")
-    return offsets, sorted_pair[:P], inv[:P], tiles, ntiles
+    return offsets, sorted_pair[:P], inv[:P], tiles, sched
 
 
-def moe_grouped_gemm_swiglu(cfg, x, x_scale, w1, w1_scale, sorted_pair, tiles, ntiles):
+def moe_grouped_gemm_swiglu(cfg, x, x_scale, w1, w1_scale, sorted_pair, tiles, sched):
     dev = x.device
     _expect(x, (cfg.T, cfg.H), _payload(cfg), "x")
     _expect(w1, (cfg.EL, 2 * cfg.I, cfg.H), _payload(cfg), "w1")
     act = torch.empty((cfg.P, cfg.I), dtype=_payload(cfg), device=dev)
     act_scale = torch.empty((cfg.P, cfg.I // 128), dtype=torch.float32, device=dev) if cfg.dtype == 1 else None
     rc = load().moe_grouped_gemm_swiglu(C.byref(cfg), _p(x), _p(x_scale), _p(w1), _p(w1_scale), _p(sorted_pair),
-                                        _p(tiles), _p(ntiles), _p(act), _p(act_scale), _stream())
+                                        _p(tiles), _p(sched), _p(act), _p(act_scale), _stream())
     _check(rc, "moe_grouped_gemm_swiglu")
     return act, act_scale
 
 
-def moe_grouped_gemm_down(cfg, act, act_scale, w2, w2_scale, tiles, ntiles):
+def moe_grouped_gemm_down(cfg, act, act_scale, w2, w2_scale, tiles, sched):
     dev = act.device
     _expect(act, (cfg.P, cfg.I), _payload(cfg), "act")
     _expect(w2, (cfg.EL, cfg.H, cfg.I), _payload(cfg), "w2")
     y = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device=dev)
     rc = load().moe_grouped_gemm_down(C.byref(cfg), _p(act), _p(act_scale), _p(w2), _p(w2_scale), _p(tiles),
-                                      _p(ntiles), _p(y), _stream())
+                                      _p(sched), _p(y), _stream())
     _check(rc, "moe_grouped_gemm_down")
     return y
 

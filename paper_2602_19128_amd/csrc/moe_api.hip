@@ -62,7 +62,7 @@ int max_tiles_for(const moe_config &c)
 
 // Workspace sections of moe_forward, in order, each 256-byte aligned.
 struct Layout {
-    size_t route, ids, w, offsets, sorted_pair, inv, tiles, ntiles, act, act_scale, y, xq, xq_scale, total;
+    size_t route, ids, w, offsets, sorted_pair, inv, tiles, sched, act, act_scale, y, xq, xq_scale, total;
 };
 
 // The problem as the router sees it: with quantise-on-the-path the router scores the bf16 hidden
@@ -88,7 +88,7 @@ Layout layout_for(const moe_config &c)
     l.sorted_pair = take(P * sizeof(int32_t));
     l.inv = take(P * sizeof(int32_t));
     l.tiles = take((size_t)max_tiles_for(c) * sizeof(moe_tile));
-    l.ntiles = take(sizeof(int32_t));
+    l.sched = take(MOE_SCHED_INTS * sizeof(int32_t));
     l.act = take(P * c.I * act_elem);
     l.act_scale = take(c.dtype == MOE_DTYPE_FP8_E4M3 ? P * (c.I / kQBlock) * sizeof(float) : 0);
     l.y = take(P * c.H * 2);
@@ -143,40 +143,40 @@ int moe_quantize_act(const moe_config *cfg, const void *x, void *xq_out, float *
 }
 
 int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out, int32_t *sorted_pair_out,
-                int32_t *inv_out, moe_tile *tiles_out, int32_t *ntiles_out, void *stream)
+                int32_t *inv_out, moe_tile *tiles_out, int32_t *sched_out, void *stream)
 {
     int rc = validate(cfg);
     if (rc != MOE_OK) return rc;
-    if (!offsets_out || !ntiles_out) return MOE_ERR_INVALID;
+    if (!offsets_out || !sched_out) return MOE_ERR_INVALID;
     if (cfg->T > 0 && (!ids || !sorted_pair_out || !inv_out || !tiles_out)) return MOE_ERR_INVALID;
     return launch_permute(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), ids, offsets_out, sorted_pair_out,
-                          inv_out, tiles_out, ntiles_out, (hipStream_t)stream);
+                          inv_out, tiles_out, sched_out, (hipStream_t)stream);
 }
 
 int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x_scale, const void *w1,
                             const float *w1_scale, const int32_t *sorted_pair, const moe_tile *tiles,
-                            const int32_t *ntiles, void *act_out, float *act_scale_out, void *stream)
+                            const int32_t *sched, void *act_out, float *act_scale_out, void *stream)
 {
     int rc = validate(cfg);
     if (rc != MOE_OK) return rc;
     if (cfg->T == 0) return MOE_OK;
-    if (!x || !w1 || !sorted_pair || !tiles || !ntiles || !act_out) return MOE_ERR_INVALID;
+    if (!x || !w1 || !sorted_pair || !tiles || !sched || !act_out) return MOE_ERR_INVALID;
     if (fp8(cfg) && (!x_scale || !w1_scale || !act_scale_out)) return MOE_ERR_INVALID;
     return launch_gemm_swiglu(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), x, x_scale, w1, w1_scale,
-                              sorted_pair, tiles, ntiles, act_out, act_scale_out, (hipStream_t)stream);
+                              sorted_pair, tiles, sched, act_out, act_scale_out, (hipStream_t)stream);
 }
 
 int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *act_scale, const void *w2,
-                          const float *w2_scale, const moe_tile *tiles, const int32_t *ntiles, void *y_out,
+                          const float *w2_scale, const moe_tile *tiles, const int32_t *sched, void *y_out,
                           void *stream)
 {
     int rc = validate(cfg);
     if (rc != MOE_OK) return rc;
     if (cfg->T == 0) return MOE_OK;
-    if (!act || !w2 || !tiles || !ntiles || !y_out) return MOE_ERR_INVALID;
+    if (!act || !w2 || !tiles || !sched || !y_out) return MOE_ERR_INVALID;
     if (fp8(cfg) && (!act_scale || !w2_scale)) return MOE_ERR_INVALID;
     return launch_gemm_down(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), act, act_scale, w2, w2_scale, tiles,
-                            ntiles, y_out, (hipStream_t)stream);
+                            sched, y_out, (hipStream_t)stream);
 }
 
 int moe_combine(const moe_config *cfg, const void *y, const float *w, const int32_t *inv, void *out,
@@ -210,7 +210,7 @@ int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scal
     int32_t *sorted_pair = reinterpret_cast<int32_t *>(ws + l.sorted_pair);
     int32_t *inv = reinterpret_cast<int32_t *>(ws + l.inv);
     moe_tile *tiles = reinterpret_cast<moe_tile *>(ws + l.tiles);
-    int32_t *ntiles = reinterpret_cast<int32_t *>(ws + l.ntiles);
+    int32_t *sched = reinterpret_cast<int32_t *>(ws + l.sched);
     void *act = ws + l.act;
     float *act_scale = fp8(cfg) ? reinterpret_cast<float *>(ws + l.act_scale) : nullptr;
     void *y = ws + l.y;
@@ -238,11 +238,11 @@ int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scal
     }
     rc = launch_route(router_view(*cfg), x_route, x_route_scale, router_w, bias, ids, w, ws + l.route, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
-    rc = launch_permute(*cfg, tr, mt, ids, offsets, sorted_pair, inv, tiles, ntiles, s);
+    rc = launch_permute(*cfg, tr, mt, ids, offsets, sorted_pair, inv, tiles, sched, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
-    rc = launch_gemm_swiglu(*cfg, tr, mt, x, x_scale, w1, w1_scale, sorted_pair, tiles, ntiles, act, act_scale, s);
+    rc = launch_gemm_swiglu(*cfg, tr, mt, x, x_scale, w1, w1_scale, sorted_pair, tiles, sched, act, act_scale, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
-    rc = launch_gemm_down(*cfg, tr, mt, act, act_scale, w2, w2_scale, tiles, ntiles, y, s);
+    rc = launch_gemm_down(*cfg, tr, mt, act, act_scale, w2, w2_scale, tiles, sched, y, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
     rc = launch_combine(*cfg, y, w, inv, out, s);
     if (rc != MOE_OK) return rc;

@@ -40,8 +40,9 @@
 //  * Workgroups start their K loops at different columns when the row stride is a multiple of
 //    4 KiB (see k_groups_for).
 //
-// Workgroups are numbered so that each XCD (own L2) gets a contiguous range of the
-// (expert tile, column slab) work: the token rows of an expert stay in one L2.
+// The tile list arrives as a schedule of eight work ranges, tallest tiles first (moe_permute);
+// workgroups are numbered so that each XCD (own L2) works through one range: the token rows of
+// an expert stay in one L2, and the tiles that take longest start first.
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -53,7 +54,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 constexpr int GM_STEP_BYTES = 128;        // bytes of every row consumed per K step
-constexpr int GM_XCDS = 8;
+constexpr int GM_XCDS = MOE_WORK_RANGES;  // one work range of the schedule per XCD
 constexpr int GM_W_COPIES = 4;            // weight copies per wavefront per step: 32 rows, 8 rows each
 constexpr int GM_W_STAGE = 32 * 128;      // bytes of one wavefront's weight stage
 constexpr int GM_CUS = 256;
@@ -502,30 +503,39 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
     }
 }
 
+// Work range r of the schedule (see moe_permute) belongs to the workgroups with blockIdx % 8 == r,
+// which the hardware places on one XCD: the workgroups that run side by side there are on
+// neighbouring column slabs of the same expert tile and share its token rows through that L2,
+// and every XCD starts with its tallest tiles.  The launch normally has one workgroup per
+// (tile, column slab); the loop only matters when a range holds more work than its share of the
+// grid.
 template <class SH>
 __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
-                                                                   const int32_t *__restrict__ ntiles, int col_tiles)
+                                                                   const int32_t *__restrict__ sched, int col_tiles)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int total = *ntiles * col_tiles;
-    const int per_xcd = ceil_div(total, GM_XCDS);
-    const int slot = blockIdx.x / GM_XCDS;
-    if (slot >= per_xcd) return;
-    const int work = (blockIdx.x % GM_XCDS) * per_xcd + slot;
-    if (work >= total) return;
-    const moe_tile head = tiles[work / col_tiles];
-    const int local = work - head.first * col_tiles;           // index inside this expert's work
-    const int ct = local / head.count;                         // column slab
-    const moe_tile tile = tiles[head.first + local % head.count];
-    const int nb = ceil_div(tile.rows, 16);
-    dispatch_blocks<SH, 1>(nb, g, tile, ct, work, smem);
+    const int range = blockIdx.x % MOE_WORK_RANGES;
+    const int tile0 = sched[1 + range];
+    const int items = (sched[2 + range] - tile0) * col_tiles;
+    const int stride = gridDim.x / MOE_WORK_RANGES;
+    for (int slot = blockIdx.x / MOE_WORK_RANGES; slot < items; slot += stride) {
+        const int work = tile0 * col_tiles + slot;
+        const moe_tile head = tiles[work / col_tiles];
+        const int local = work - head.first * col_tiles;       // index inside this expert's work
+        const int ct = local / head.count;                     // column slab
+        const moe_tile tile = tiles[head.first + local % head.count];
+        const int nb = ceil_div(tile.rows, 16);
+        dispatch_blocks<SH, 1>(nb, g, tile, ct, work, smem);
+        __syncthreads();                                       // the output tile has left LDS
+    }
 }
 
 template <class SH>
-int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles, int max_tiles, hipStream_t s)
+int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched, int max_tiles, hipStream_t s)
 {
     const int col_tiles = ceil_div(g.n_out, SH::COLS);
-    const int blocks = ceil_div(max_tiles * col_tiles, GM_XCDS) * GM_XCDS;
+    // a range holds about an eighth of the tiles; a little slack keeps the loop in the kernel at one trip
+    const int blocks = (ceil_div(max_tiles, GM_XCDS) + 1) * col_tiles * GM_XCDS;
     auto kern = grouped_gemm_kernel<SH>;
     static bool attr_done = false;          // raise the dynamic-LDS limit once per variant
     if (!attr_done) {
@@ -534,14 +544,14 @@ int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles
         if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, ntiles, col_tiles);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, sched, col_tiles);
     return check_launch();
 }
 
 // Narrow (4-wavefront) workgroups when the wide ones would leave compute units without work
 // (not for the fp8 gate/up GEMM, whose epilogue needs a whole 128-column block per workgroup).
 template <int MB_MAX, bool SWIGLU, bool FP8>
-int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles, int max_tiles, int est_tiles,
+int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched, int max_tiles, int est_tiles,
                     hipStream_t s)
 {
     constexpr int DA = MB_MAX >= 16 ? 1 : 2;                  // 16 row blocks: 32 KiB per token stage
@@ -550,21 +560,21 @@ int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *nti
     if constexpr (!(FP8 && SWIGLU)) {
         using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU, FP8>;
         const long wide_wgs = (long)est_tiles * ceil_div(g.n_out, Wide::COLS);
-        if (wide_wgs < 2 * GM_CUS) return launch_shape<Narrow>(g, tiles, ntiles, max_tiles, s);
+        if (wide_wgs < 2 * GM_CUS) return launch_shape<Narrow>(g, tiles, sched, max_tiles, s);
     }
-    return launch_shape<Wide>(g, tiles, ntiles, max_tiles, s);
+    return launch_shape<Wide>(g, tiles, sched, max_tiles, s);
 }
 
 template <bool SWIGLU, bool FP8>
-int launch_by_tile_rows(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *ntiles,
+int launch_by_tile_rows(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
                         int max_tiles, int est_tiles, hipStream_t s)
 {
     switch (tile_rows) {
-    case 256: return launch_for_rows<16, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 128: return launch_for_rows<8, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 64:  return launch_for_rows<4, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 32:  return launch_for_rows<2, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
-    case 16:  return launch_for_rows<1, SWIGLU, FP8>(g, tiles, ntiles, max_tiles, est_tiles, s);
+    case 256: return launch_for_rows<16, SWIGLU, FP8>(g, tiles, sched, max_tiles, est_tiles, s);
+    case 128: return launch_for_rows<8, SWIGLU, FP8>(g, tiles, sched, max_tiles, est_tiles, s);
+    case 64:  return launch_for_rows<4, SWIGLU, FP8>(g, tiles, sched, max_tiles, est_tiles, s);
+    case 32:  return launch_for_rows<2, SWIGLU, FP8>(g, tiles, sched, max_tiles, est_tiles, s);
+    case 16:  return launch_for_rows<1, SWIGLU, FP8>(g, tiles, sched, max_tiles, est_tiles, s);
     default:  return MOE_ERR_UNSUPPORTED;
     }
 }
@@ -596,7 +606,7 @@ int nt_output(size_t bytes) { return bytes > (size_t)32 << 20 ? 1 : 0; }
 
 int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const void *x,
                        const float *x_scale, const void *w1, const float *w1_scale, const int32_t *sorted_pair,
-                       const moe_tile *tiles, const int32_t *ntiles, void *act, float *act_scale, hipStream_t s)
+                       const moe_tile *tiles, const int32_t *sched, void *act, float *act_scale, hipStream_t s)
 {
     GemmArgs g{static_cast<const unsigned char *>(x), x_scale, static_cast<const unsigned char *>(w1), w1_scale,
                sorted_pair, static_cast<unsigned char *>(act), act_scale, c.H, c.I, c.top_k,
@@ -604,13 +614,13 @@ int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const 
                nt_output((size_t)c.T * c.top_k * c.I * (c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2))};
     if (c.dtype == MOE_DTYPE_FP8_E4M3) {
         if (c.H > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;  // weight scales of one slab sit in two registers
-        return launch_by_tile_rows<true, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+        return launch_by_tile_rows<true, true>(tile_rows, g, tiles, sched, max_tiles, expected_tiles(c), s);
     }
-    return launch_by_tile_rows<true, false>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+    return launch_by_tile_rows<true, false>(tile_rows, g, tiles, sched, max_tiles, expected_tiles(c), s);
 }
 
 int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const void *act, const float *act_scale,
-                     const void *w2, const float *w2_scale, const moe_tile *tiles, const int32_t *ntiles, void *y,
+                     const void *w2, const float *w2_scale, const moe_tile *tiles, const int32_t *sched, void *y,
                      hipStream_t s)
 {
     GemmArgs g{static_cast<const unsigned char *>(act), act_scale, static_cast<const unsigned char *>(w2), w2_scale,
@@ -619,9 +629,9 @@ int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const vo
                nt_output((size_t)c.T * c.top_k * c.H * 2)};
     if (c.dtype == MOE_DTYPE_FP8_E4M3) {
         if (c.I > 128 * kQBlock) return MOE_ERR_UNSUPPORTED;
-        return launch_by_tile_rows<false, true>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+        return launch_by_tile_rows<false, true>(tile_rows, g, tiles, sched, max_tiles, expected_tiles(c), s);
     }
-    return launch_by_tile_rows<false, false>(tile_rows, g, tiles, ntiles, max_tiles, expected_tiles(c), s);
+    return launch_by_tile_rows<false, false>(tile_rows, g, tiles, sched, max_tiles, expected_tiles(c), s);
 }
 
 }  // namespace moe

@@ -52,14 +52,14 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
 int launch_quantize_act(const moe_config &c, const void *x, void *xq, float *x_scale, hipStream_t s);
 int launch_permute(const moe_config &c, int tile_rows, int max_tiles, const int32_t *ids,
                    int32_t *offsets, int32_t *sorted_pair, int32_t *inv, moe_tile *tiles,
-                   int32_t *ntiles, hipStream_t s);
+                   int32_t *sched, hipStream_t s);
 int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const void *x,
                        const float *x_scale, const void *w1, const float *w1_scale,
-                       const int32_t *sorted_pair, const moe_tile *tiles, const int32_t *ntiles,
+                       const int32_t *sorted_pair, const moe_tile *tiles, const int32_t *sched,
                        void *act, float *act_scale, hipStream_t s);
 int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const void *act,
                      const float *act_scale, const void *w2, const float *w2_scale,
-                     const moe_tile *tiles, const int32_t *ntiles, void *y, hipStream_t s);
+                     const moe_tile *tiles, const int32_t *sched, void *y, hipStream_t s);
 int launch_combine(const moe_config &c, const void *y, const float *w, const int32_t *inv, void *out,
                    hipStream_t s);
 

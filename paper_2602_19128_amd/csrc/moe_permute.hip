@@ -6,6 +6,13 @@
 // ranks equal experts inside a 64-pair batch with ballots.  The same kernel cuts
 // every non-empty expert segment into row tiles for the grouped GEMMs; experts
 // without tokens get no tile and therefore cost nothing downstream.
+//
+// The tile list is also the GEMMs' schedule.  A tile's cost grows with its rows, and a launch
+// ends when its last tile ends, so experts are ranked by row count (largest first) and dealt in
+// snake order (0..7, 7..0, ...) to eight work ranges, one per XCD: every range starts with its
+// tallest tiles and the eight ranges carry about the same load.  All tiles of an expert stay in
+// one range (its workgroups share the expert's token rows, and the weights of an expert with
+// several tiles, through that XCD's L2).
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -37,13 +44,19 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
                                                              int32_t *__restrict__ sorted_pair,
                                                              int32_t *__restrict__ inv,
                                                              moe_tile *__restrict__ tiles,
-                                                             int32_t *__restrict__ ntiles)
+                                                             int32_t *__restrict__ sched)
 {
     extern __shared__ int lds[];
     int *wcount = lds;                         // [PM_WAVES][E]  per-wavefront counts -> write cursors
     int *scan_a = wcount + PM_WAVES * E;       // [E]
     int *scan_b = scan_a + E;                  // [E]
     int *first_row = scan_b + E;               // [E+1] exclusive offsets
+    const int RQ = ceil_div(E, MOE_WORK_RANGES); // schedule positions per work range
+    const int EQ = RQ * MOE_WORK_RANGES;
+    int *rows_of = first_row + E + 1;          // [E]  rows per expert, for the ranking
+    int *rank_of = rows_of + E;                // [E]  experts that come earlier in the ranking
+    int *sch_a = rank_of + E;                  // [EQ] tiles at each schedule position (range-major)
+    int *sch_b = sch_a + EQ;                   // [EQ]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int per_wave = ceil_div(ceil_div(P, PM_WAVES), kWave) * kWave;
@@ -80,13 +93,43 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
     }
     __syncthreads();
 
-    // tile list: expert e gets ceil(rows_e / tile_rows) records, experts in ascending order
+    // tile list: expert e gets ceil(rows_e / tile_rows) records.  Schedule position of an expert:
+    // rank by rows (descending, ties by index), dealt in snake order to the work ranges.
     const int my_tiles = (tid < E) ? ceil_div(total, tile_rows) : 0;
-    if (tid < E) scan_a[tid] = my_tiles;
+    if (tid < E) { rows_of[tid] = total; rank_of[tid] = 0; }
+    for (int i = tid; i < EQ; i += PM_THREADS) sch_a[i] = 0;
     __syncthreads();
-    block_inclusive_scan(scan_a, scan_b, E, tid);
+    // rank of expert e = experts with more rows (or as many and a lower index); the comparisons of
+    // one expert are spread over PM_THREADS / E threads
+    {
+        const int parts = max(1, PM_THREADS / E);
+        const int seg = ceil_div(E, parts);
+        const int e = tid % E, part = tid / E;
+        if (part < parts) {
+            const int mine = rows_of[e];
+            const int lo = part * seg, hi = min(E, lo + seg);
+            int before = 0;
+#pragma unroll 8
+            for (int e2 = lo; e2 < hi; ++e2) {
+                const int r2 = rows_of[e2];
+                before += (r2 > mine || (r2 == mine && e2 < e)) ? 1 : 0;
+            }
+            if (before) atomicAdd(&rank_of[e], before);
+        }
+    }
+    __syncthreads();
+    int q = 0;
     if (tid < E) {
-        const int first = scan_a[tid] - my_tiles;
+        const int rank = rank_of[tid];
+        const int round = rank / MOE_WORK_RANGES, pos = rank % MOE_WORK_RANGES;
+        const int range = (round & 1) ? MOE_WORK_RANGES - 1 - pos : pos;
+        q = range * RQ + round;
+        sch_a[q] = my_tiles;
+    }
+    __syncthreads();
+    block_inclusive_scan(sch_a, sch_b, EQ, tid);
+    if (tid < E) {
+        const int first = sch_a[q] - my_tiles;
         // an expert with more rows than a tile is cut into equal parts (rounded up to whole MFMA
         // row blocks): the grouped GEMMs' step time grows with the rows of a tile
         const int part = my_tiles > 0 ? ceil_div(ceil_div(total, my_tiles), 16) * 16 : 0;
@@ -100,7 +143,12 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
             rec.pad0 = rec.pad1 = rec.pad2 = 0;
             tiles[first + i] = rec;
         }
-        if (tid == E - 1) *ntiles = min(scan_a[tid], max_tiles);
+    }
+    if (tid <= MOE_WORK_RANGES) {              // [0] records written, [1 + r] first record of range r (r = 8: the end)
+        const int upto = tid * RQ;             // schedule positions before range `tid`
+        const int at = upto > 0 ? sch_a[upto - 1] : 0;
+        sched[1 + tid] = min(at, max_tiles);
+        if (tid == MOE_WORK_RANGES) sched[0] = min(at, max_tiles);
     }
 
     // pass 2: stable placement.  Batches of 64 consecutive pairs; inside a batch a pair's
@@ -133,14 +181,15 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
 
 int launch_permute(const moe_config &c, int tile_rows, int max_tiles, const int32_t *ids,
                    int32_t *offsets, int32_t *sorted_pair, int32_t *inv, moe_tile *tiles,
-                   int32_t *ntiles, hipStream_t s)
+                   int32_t *sched, hipStream_t s)
 {
     const int P = c.T * c.top_k;
     const int el = local_experts(c);
-    const size_t lds = sizeof(int) * ((size_t)PM_WAVES * el + 3 * (size_t)el + 1);
+    const size_t eq = (size_t)ceil_div(el, MOE_WORK_RANGES) * MOE_WORK_RANGES;
+    const size_t lds = sizeof(int) * ((size_t)PM_WAVES * el + 5 * (size_t)el + 1 + 2 * eq);
     hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PM_THREADS), lds, s, ids, P, el, c.local_expert_offset,
                        tile_rows, max_tiles,
-                       offsets, sorted_pair, inv, tiles, ntiles);
+                       offsets, sorted_pair, inv, tiles, sched);
     return check_launch();
 }
 

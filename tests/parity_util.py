@@ -60,24 +60,49 @@ def compare_routing(ids_gpu, w_gpu, ids_ref, w_ref, margin, routed_scale=1.0, n_
     return int((~same_set).sum()), int((same_set & ~exact).sum()), same_set
 
 
-def check_tiles(tiles, ntiles, offsets_ref, tile_rows):
-    """The tile list covers every non-empty expert segment exactly, in order."""
-    n = int(ntiles.cpu().item())
+def check_tiles(tiles, sched, offsets_ref, tile_rows):
+    """The tile list covers every non-empty expert segment exactly once, cut as documented, and is a
+    valid schedule: an expert's records are consecutive and lie in one work range, experts are dealt
+    to the eight ranges in snake order of their row count (largest first, equal counts by index), and
+    every range lists its experts in that order."""
+    hdr = sched.cpu().numpy()
+    n = int(hdr[0])
     rec = tiles.cpu().numpy()[:n]
-    want = []
     E = len(offsets_ref) - 1
+    rows_of = np.diff(np.asarray(offsets_ref, dtype=np.int64))
+    want = {}                              # expert -> list of (row0, rows)
     for e in range(E):
         lo, hi = int(offsets_ref[e]), int(offsets_ref[e + 1])
         cnt = -(-(hi - lo) // tile_rows)
-        first = len(want)
         part = -(-(-(-(hi - lo) // cnt) if cnt else 0) // 16) * 16    # equal parts, whole 16-row blocks
+        cuts = []
         for i in range(cnt):
             r0 = lo + i * part
             assert hi - r0 > 0
-            want.append([e, r0, min(part, hi - r0), first, cnt])
-    assert n == len(want), f"{n} tiles, expected {len(want)}"
-    if n:
-        assert np.array_equal(rec[:, :5], np.array(want, dtype=np.int32))
+            cuts.append((r0, min(part, hi - r0)))
+        if cuts:
+            want[e] = cuts
+    assert n == sum(len(c) for c in want.values()), f"{n} tiles, expected {sum(len(c) for c in want.values())}"
+    # the ranges tile [0, n) in order
+    starts = hdr[1:10].astype(np.int64)
+    assert starts[0] == 0 and starts[8] == n and (np.diff(starts) >= 0).all(), f"bad work ranges {starts}"
+    # snake dealing of the experts ranked by rows (stable: equal rows keep index order)
+    order = sorted(want, key=lambda e: (-rows_of[e], e))
+    expect = [[] for _ in range(8)]
+    for rank, e in enumerate(order):
+        rnd, pos = divmod(rank, 8)
+        expect[7 - pos if rnd % 2 else pos].append(e)
+    at = 0
+    for r in range(8):
+        assert at == starts[r], f"range {r} starts at {starts[r]}, expected {at}"
+        for e in expect[r]:
+            cuts = want[e]
+            got = rec[at:at + len(cuts)]
+            assert (got[:, 0] == e).all() and (got[:, 3] == at).all() and (got[:, 4] == len(cuts)).all(), \
+                f"records of expert {e} at {at}: {got[:, :5]}"
+            assert [tuple(x) for x in got[:, 1:3]] == cuts, f"expert {e}: cuts {got[:, 1:3]} expected {cuts}"
+            at += len(cuts)
+    assert at == n
     return n
 
 

@@ -203,7 +203,7 @@ def test_forward_zero_tokens_and_errors():
     ids = torch.empty((0, 2), dtype=torch.int32, device="cuda")
     off, sp, inv, tiles, ntiles = moe.moe_permute(cfg, ids)
     torch.cuda.synchronize()
-    assert off.cpu().tolist() == [0] * 9 and int(ntiles.item()) == 0
+    assert off.cpu().tolist() == [0] * 9 and ntiles.cpu().tolist()[:10] == [0] * 10
     # workspace one byte short is refused before anything is enqueued
     wl = syn.WORKLOADS["tiny"]
     gpu = syn.make_inputs(wl, seed=0).to("cuda")
