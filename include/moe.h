@@ -102,7 +102,10 @@ typedef struct moe_tile {
  *                 (the last entry is the end: equal to sched[0])
  * Experts are ranked by their row count, largest first (equal counts: lower index
  * first), and dealt to the ranges in snake order (0..7, 7..0, ...), so every range
- * lists its tallest tiles first and the ranges carry similar loads. */
+ * lists its tallest tiles first and the ranges carry similar loads.  The grouped
+ * GEMMs give range r to XCD r when a range is a few tiles, and otherwise cut the
+ * list into eight parts of equal tile-slab count (the ranges, up to a tile or two
+ * at their ends). */
 enum { MOE_WORK_RANGES = 8, MOE_SCHED_INTS = 16 };
 
 /* Bytes of device scratch moe_route / moe_forward need for this problem. */
