@@ -533,8 +533,25 @@ __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, c
         items = min(per, total - first);
     }
     const int stride = gridDim.x / MOE_WORK_RANGES;
-    for (int slot = blockIdx.x / MOE_WORK_RANGES; slot < items; slot += stride) {
-        const int work = first + slot;
+    // Order inside a long part: alternating between its front and its back in chunks of col_tiles
+    // items (tall tile, short tile, tall, ...) instead of tallest-first.  Tall tiles spend their
+    // time on LDS and the matrix cores, short ones on the weight stream, and a mix of both running
+    // side by side is faster than all tall tiles together: gate/up GEMM -4..5 % on the DeepSeek-shaped
+    // prefills; the down GEMM -12 % when the tallest tiles are full height (hot experts), but +5 % when
+    // every tile is low, where tallest-first only shortens the tail - so it alternates only when the
+    // tallest tile of the list (its first record) has more than 128 rows.
+    const bool zigzag = !whole_ranges && (SH::SWIGLU || tiles[0].rows > 128);
+    const int nchunks = ceil_div(items, col_tiles);
+    const int slots = zigzag ? nchunks * col_tiles : items;
+    for (int slot = blockIdx.x / MOE_WORK_RANGES; slot < slots; slot += stride) {
+        int pos = slot;
+        if (zigzag) {
+            const int c = slot / col_tiles;
+            const int pc = (c & 1) ? nchunks - 1 - (c >> 1) : (c >> 1);
+            pos = pc * col_tiles + slot % col_tiles;
+            if (pos >= items) continue;                        // the part's last chunk may be short
+        }
+        const int work = first + pos;
         const moe_tile head = tiles[work / col_tiles];
         const int local = work - head.first * col_tiles;       // index inside this expert's work
         const int ct = local / head.count;                     // column slab
