@@ -1,11 +1,15 @@
 // Sort-scatter (paper Sec. 4.5: tokens reordered by expert into contiguous memory).
 //
-// One workgroup of 16 wavefronts does a stable counting sort of the P (token, slot)
-// pairs by expert id entirely in LDS: per-wavefront histograms, a prefix scan over
-// experts, then each wavefront walks its contiguous slice of pairs in order and
-// ranks equal experts inside a 64-pair batch with ballots.  The same kernel cuts
-// every non-empty expert segment into row tiles for the grouped GEMMs; experts
-// without tokens get no tile and therefore cost nothing downstream.
+// A stable counting sort of the P (token, slot) pairs by expert id.  The pairs are cut into
+// slices of PM_SLICE, one workgroup of 16 wavefronts each, and the workgroups never talk to each
+// other: every workgroup counts ALL pairs in LDS (how many of each expert lie before its slice,
+// inside it per wavefront, and after it), which gives it the expert offsets and the first row
+// of each of its wavefronts; then each wavefront walks its contiguous part of the slice in
+// order and ranks equal experts inside a 64-pair batch with ballots.  Counting everything in
+// every workgroup costs a few microseconds; placing the pairs is the expensive part (it is bound
+// by the instruction rate of a compute unit) and is what the slices divide.  Workgroup 0 also
+// writes the offsets and cuts every non-empty expert segment into row tiles for the grouped
+// GEMMs; experts without tokens get no tile and therefore cost nothing downstream.
 //
 // The tile list is also the GEMMs' schedule.  A tile's cost grows with its rows, and a launch
 // ends when its last tile ends, so experts are ranked by row count (largest first) and dealt in
@@ -20,6 +24,9 @@ namespace {
 
 constexpr int PM_THREADS = 1024;
 constexpr int PM_WAVES = PM_THREADS / kWave;
+constexpr int PM_BATCH = 8;             // 64-pair batches whose ids are loaded together
+constexpr int PM_SLICE = 2048;          // pairs placed by one workgroup
+constexpr int PM_MAX_WGS = 64;
 
 // Inclusive scan of n <= kMaxExperts ints held in LDS (Hillis-Steele, all threads sync).
 __device__ inline void block_inclusive_scan(int *a, int *b, int n, int tid)
@@ -55,44 +62,67 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
     const int EQ = RQ * MOE_WORK_RANGES;
     int *rows_of = first_row + E + 1;          // [E]  rows per expert, for the ranking
     int *rank_of = rows_of + E;                // [E]  experts that come earlier in the ranking
-    int *sch_a = rank_of + E;                  // [EQ] tiles at each schedule position (range-major)
+    int *before = rank_of + E;                 // [E]  pairs of each expert in earlier slices
+    int *after = before + E;                   // [E]  ... in later slices
+    int *sch_a = after + E;                    // [EQ] tiles at each schedule position (range-major)
     int *sch_b = sch_a + EQ;                   // [EQ]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int per_wave = ceil_div(ceil_div(P, PM_WAVES), kWave) * kWave;
-    const int p_beg = min(P, wave * per_wave), p_end = min(P, p_beg + per_wave);
+    // this workgroup's slice, and this wavefront's part of it (whole 64-pair batches)
+    const int slice = ceil_div(ceil_div(P, (int)gridDim.x), PM_WAVES * kWave) * PM_WAVES * kWave;
+    const int s_beg = min(P, (int)blockIdx.x * slice), s_end = min(P, s_beg + slice);
+    const int per_wave = slice / PM_WAVES;
+    const int p_beg = min(s_end, s_beg + wave * per_wave), p_end = min(s_end, p_beg + per_wave);
+    const bool lead = blockIdx.x == 0;         // the workgroup that writes offsets, tiles and schedule
 
     for (int i = tid; i < PM_WAVES * E; i += PM_THREADS) wcount[i] = 0;
+    if (tid < E) { before[tid] = 0; after[tid] = 0; }
     __syncthreads();
 
-    // pass 1: histogram of this wavefront's slice (integer LDS adds: order-independent)
-    for (int p = p_beg + lane; p < p_end; p += kWave) {
-        const int e = ids[p] - e_first;
-        if (e >= 0 && e < E) atomicAdd(&wcount[wave * E + e], 1);
+    // pass 1: count every pair once (integer LDS adds: order-independent).  The ids of PM_BATCH
+    // strides are requested together so that their latencies overlap.
+    for (int base = 0; base < P; base += PM_BATCH * PM_THREADS) {
+        int ev[PM_BATCH];
+#pragma unroll
+        for (int j = 0; j < PM_BATCH; ++j) {
+            const int p = base + j * PM_THREADS + tid;
+            ev[j] = (p < P) ? ids[p] - e_first : -1;
+        }
+#pragma unroll
+        for (int j = 0; j < PM_BATCH; ++j) {
+            const int p = base + j * PM_THREADS + tid;
+            if (ev[j] >= 0 && ev[j] < E) {
+                int *bin = p < s_beg ? before : p >= s_end ? after : wcount + ((p - s_beg) / per_wave) * E;
+                atomicAdd(&bin[ev[j]], 1);
+            }
+        }
     }
     __syncthreads();
 
-    // rows per expert -> exclusive offsets
+    // rows per expert -> exclusive offsets -> first row of each wavefront of this slice
     int total = 0;
-    if (tid < E)
+    if (tid < E) {
+        total = before[tid] + after[tid];
         for (int wv = 0; wv < PM_WAVES; ++wv) total += wcount[wv * E + tid];
-    if (tid < E) scan_a[tid] = total;
+        scan_a[tid] = total;
+    }
     __syncthreads();
     block_inclusive_scan(scan_a, scan_b, E, tid);
     if (tid < E) {
         const int excl = scan_a[tid] - total;
         first_row[tid] = excl;
-        offsets[tid] = excl;
-        int run = excl;                        // turn counts into per-wavefront write cursors
+        if (lead) offsets[tid] = excl;
+        int run = excl + before[tid];          // turn counts into per-wavefront write cursors
         for (int wv = 0; wv < PM_WAVES; ++wv) {
             const int c = wcount[wv * E + tid];
             wcount[wv * E + tid] = run;
             run += c;
         }
-        if (tid == E - 1) { first_row[E] = scan_a[tid]; offsets[E] = scan_a[tid]; }
+        if (tid == E - 1) { first_row[E] = scan_a[tid]; if (lead) offsets[E] = scan_a[tid]; }
     }
     __syncthreads();
 
+    if (lead) {
     // tile list: expert e gets ceil(rows_e / tile_rows) records.  Schedule position of an expert:
     // rank by rows (descending, ties by index), dealt in snake order to the work ranges.
     const int my_tiles = (tid < E) ? ceil_div(total, tile_rows) : 0;
@@ -150,29 +180,41 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
         sched[1 + tid] = min(at, max_tiles);
         if (tid == MOE_WORK_RANGES) sched[0] = min(at, max_tiles);
     }
+    }   // lead
 
     // pass 2: stable placement.  Batches of 64 consecutive pairs; inside a batch a pair's
     // rank among equal experts is the number of lower lanes holding the same expert.
     volatile int *cursor = wcount + wave * E;
     const int ebits = 32 - __clz(max(E - 1, 1));
-    for (int base = p_beg; base < p_end; base += kWave) {
-        const int p = base + lane;
-        const int e = (p < p_end) ? ids[p] - e_first : -1;
-        const bool valid = e >= 0 && e < E;
-        unsigned long long same = __ballot(valid);
-        for (int b = 0; b < ebits; ++b) {
-            const unsigned long long m = __ballot((e >> b) & 1);
-            same &= ((e >> b) & 1) ? m : ~m;
+    for (int base0 = p_beg; base0 < p_end; base0 += PM_BATCH * kWave) {
+        int ev[PM_BATCH];
+#pragma unroll
+        for (int j = 0; j < PM_BATCH; ++j) {
+            const int p = base0 + j * kWave + lane;
+            ev[j] = (p < p_end) ? ids[p] - e_first : -1;
         }
-        const unsigned long long lower = (1ull << lane) - 1ull;
-        if (valid) {
-            const int rank = __popcll(same & lower);
-            const int row = cursor[e] + rank;
-            sorted_pair[row] = p;
-            inv[p] = row;
-            if (rank == 0) cursor[e] = cursor[e] + __popcll(same);   // one lane per expert advances it
-        } else if (p < p_end) {
-            inv[p] = -1;
+#pragma unroll
+        for (int j = 0; j < PM_BATCH; ++j) {
+            const int base = base0 + j * kWave;
+            if (base >= p_end) break;                          // wave-uniform
+            const int p = base + lane;
+            const int e = ev[j];
+            const bool valid = e >= 0 && e < E;
+            unsigned long long same = __ballot(valid);
+            for (int b = 0; b < ebits; ++b) {
+                const unsigned long long m = __ballot((e >> b) & 1);
+                same &= ((e >> b) & 1) ? m : ~m;
+            }
+            const unsigned long long lower = (1ull << lane) - 1ull;
+            if (valid) {
+                const int rank = __popcll(same & lower);
+                const int row = cursor[e] + rank;
+                sorted_pair[row] = p;
+                inv[p] = row;
+                if (rank == 0) cursor[e] = cursor[e] + __popcll(same);   // one lane per expert advances it
+            } else if (p < p_end) {
+                inv[p] = -1;
+            }
         }
     }
 }
@@ -186,8 +228,9 @@ int launch_permute(const moe_config &c, int tile_rows, int max_tiles, const int3
     const int P = c.T * c.top_k;
     const int el = local_experts(c);
     const size_t eq = (size_t)ceil_div(el, MOE_WORK_RANGES) * MOE_WORK_RANGES;
-    const size_t lds = sizeof(int) * ((size_t)PM_WAVES * el + 5 * (size_t)el + 1 + 2 * eq);
-    hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PM_THREADS), lds, s, ids, P, el, c.local_expert_offset,
+    const size_t lds = sizeof(int) * ((size_t)PM_WAVES * el + 7 * (size_t)el + 1 + 2 * eq);
+    const int wgs = min(PM_MAX_WGS, max(1, ceil_div(P, PM_SLICE)));
+    hipLaunchKernelGGL(permute_kernel, dim3(wgs), dim3(PM_THREADS), lds, s, ids, P, el, c.local_expert_offset,
                        tile_rows, max_tiles,
                        offsets, sorted_pair, inv, tiles, sched);
     return check_launch();
