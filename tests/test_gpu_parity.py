@@ -237,3 +237,32 @@ def test_permute_drops_out_of_range_ids_and_handles_one_hot_expert():
     off_r, sp_r, inv_r = orc.permute(ids, 8)
     assert np.array_equal(off.cpu().numpy(), off_r) and np.array_equal(sp.cpu().numpy(), sp_r)
     check_tiles(tiles, ntiles, off_r, moe.moe_tile_rows(cfg))
+
+
+@pytest.mark.parametrize("T, k, E, lo, n", [(2500, 8, 256, 0, 0), (3001, 6, 64, 16, 24), (9000, 8, 512, 0, 0),
+                                            (2049, 1, 3, 0, 0)])
+def test_permute_many_pairs_over_several_workgroups(T, k, E, lo, n):
+    """Enough pairs that the sort-scatter runs as several independent workgroups: ragged last
+    slice, ids outside the (local) expert range, experts without tokens, a heavily loaded expert."""
+    wl = syn.Workload("many_pairs", T=T, H=128, I=64, E=E, top_k=k, local_offset=lo, local_experts=n)
+    cfg = moe.MoEConfig.from_workload(wl)
+    rng = np.random.default_rng(T + E)
+    ids = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    ids[rng.random((T, k)) < 0.3] = min(5, E - 1)            # one expert far above the others
+    if E > 8:
+        ids[ids == 7] = 6                                    # an expert nobody chose
+    ids[::97, 0] = -1
+    ids[5::131, k - 1] = E
+    print(f"\n[permute] T={T} k={k} E={E} local=({lo},{n})", flush=True)
+    off, sp, inv, tiles, sched = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
+    torch.cuda.synchronize()
+    first, count = (lo, n) if n > 0 else (0, E)
+    flat = ids.reshape(-1)
+    keep = (flat >= first) & (flat < first + count)
+    off_r, sp_r, inv_r = orc.permute((flat[keep] - first).reshape(-1, 1), count)   # oracle on the kept pairs
+    kept_pairs = np.nonzero(keep)[0]
+    assert np.array_equal(off.cpu().numpy(), off_r)
+    assert np.array_equal(sp.cpu().numpy()[: keep.sum()], kept_pairs[sp_r])
+    inv_g = inv.cpu().numpy()
+    assert (inv_g[~keep] == -1).all() and np.array_equal(inv_g[keep], inv_r)
+    check_tiles(tiles, sched, off_r, moe.moe_tile_rows(cfg))
