@@ -156,7 +156,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     constexpr int SLAB = SH::SLAB;
     static_assert(GM_W_COPIES + (DA - 1) * (GM_W_COPIES + A_PASS_MAX + 1) <= 30, "wait_vmcnt_upto covers up to 30 copies in flight");
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    // The thread index goes through an empty asm statement, so that everything derived from it is
+    // computed here, per item: otherwise the compiler hoists the per-lane addresses of every
+    // row-block variant out of the kernel's item loop and keeps them all in registers at once.
+    int tid_opaque = threadIdx.x;
+    asm volatile("" : "+v"(tid_opaque));
+    const int tid = tid_opaque, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lets the compiler keep it scalar
     const int l16 = lane & 15, lq = lane >> 4;
     const int crow = lane >> 3;                               // copy: row inside an 8-row pass
