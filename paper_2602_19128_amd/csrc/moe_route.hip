@@ -502,7 +502,10 @@ __global__ __launch_bounds__(256) void router_topk_kernel(const float *__restric
 // expert, a butterfly adds them across the wavefront in a fixed order.
 constexpr int RT_FEW = 16;
 
-template <bool FP8>
+// WPT wavefronts share a token (each takes a contiguous part of H, the parts are added in wavefront
+// order): with few tokens one wavefront per token leaves most of the chip idle and is bound by the
+// latency of its own loads.
+template <bool FP8, int WPT>
 __global__ __launch_bounds__(256) void router_few_experts_kernel(const void *__restrict__ x,
                                                                  const float *__restrict__ x_scale,
                                                                  const float *__restrict__ router_w,
@@ -510,18 +513,29 @@ __global__ __launch_bounds__(256) void router_few_experts_kernel(const void *__r
                                                                  int32_t *__restrict__ ids, float *__restrict__ w,
                                                                  TopkParams p, int H)
 {
+    constexpr int TPB = 4 / WPT;                           // tokens per workgroup of four wavefronts
+    __shared__ float part_z[4][RT_FEW];
     const int lane = threadIdx.x & (kWave - 1);
-    const int t = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (t >= p.T) return;                                  // whole wave leaves together
+    const int wv = threadIdx.x / kWave;
+    const int t = blockIdx.x * TPB + wv / WPT;
+    const int sub = wv % WPT;                              // which part of H this wavefront sums
+    const bool live = t < p.T;
+    if (WPT == 1 && !live) return;                         // whole wave leaves together (no barrier below)
     const int E = p.E;
+    // parts are whole 128-element scale blocks (H is a multiple of 64; of 128 for fp8)
+    const int hpart = ((H / WPT + 127) / 128) * 128;
+    const int hbeg = min(H, sub * hpart), hend = min(H, hbeg + hpart);
     float acc[RT_FEW];
 #pragma unroll
     for (int e = 0; e < RT_FEW; ++e) acc[e] = 0.f;
     // four passes per iteration so that the loads of all of them are in flight together
-    for (int h0 = lane * 8; h0 < H; h0 += 4 * kWave * 8) {
+    for (int h0 = hbeg + lane * 8; live && h0 < hend; h0 += 4 * kWave * 8) {
         float xv[4][8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) load_x8<FP8>(x, x_scale, p.T, H, t, h0 + u * kWave * 8, xv[u]);
+        for (int u = 0; u < 4; ++u) {
+            const int h = h0 + u * kWave * 8;              // beyond this wavefront's part: zeros (h >= H gives zeros)
+            load_x8<FP8>(x, x_scale, p.T, H, t, h < hend ? h : H, xv[u]);
+        }
 #pragma unroll
         for (int e = 0; e < RT_FEW; ++e) {
             if (e < E) {
@@ -529,7 +543,7 @@ __global__ __launch_bounds__(256) void router_few_experts_kernel(const void *__r
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int h = h0 + u * kWave * 8;
-                    if (h < H) {
+                    if (h < hend) {
                         const float4 *src = reinterpret_cast<const float4 *>(router_w + (size_t)e * H + h);
                         a[u] = src[0]; b[u] = src[1];
                     } else {
@@ -554,6 +568,17 @@ __global__ __launch_bounds__(256) void router_few_experts_kernel(const void *__r
         if (e < E) {
             const float total = wave_sum_f32(acc[e]);
             if (lane == e) z[0] = total;
+        }
+    }
+    if constexpr (WPT > 1) {
+        if (lane < RT_FEW) part_z[wv][lane] = z[0];
+        __syncthreads();
+        if (sub != 0 || !live) return;
+        if (lane < RT_FEW) {
+            float total = part_z[wv][lane];
+#pragma unroll
+            for (int j = 1; j < WPT; ++j) total += part_z[wv + j][lane];
+            z[0] = total;
         }
     }
     route_token<1>(z, lane, t, bias, ids, w, p);
@@ -600,13 +625,24 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
     TopkParams p{c.T, c.E, c.top_k, c.scoring, c.renormalize, c.n_group, c.topk_group,
                  c.group_score_topn, 1, c.routed_scale};
     if (c.E <= RT_FEW) {
-        const dim3 fgrid(ceil_div(c.T, 4));
-        if (c.dtype == MOE_DTYPE_FP8_E4M3)
-            hipLaunchKernelGGL(router_few_experts_kernel<true>, fgrid, dim3(256), 0, s, x, x_scale, router_w, bias,
-                               ids, w, p, c.H);
-        else
-            hipLaunchKernelGGL(router_few_experts_kernel<false>, fgrid, dim3(256), 0, s, x, x_scale, router_w, bias,
-                               ids, w, p, c.H);
+        // few tokens: four wavefronts per token (still at least one workgroup per compute unit's worth of work)
+        const bool split = c.T <= 2048 && c.H >= 1024;
+        const dim3 fgrid(split ? c.T : ceil_div(c.T, 4));
+        if (c.dtype == MOE_DTYPE_FP8_E4M3) {
+            if (split)
+                hipLaunchKernelGGL((router_few_experts_kernel<true, 4>), fgrid, dim3(256), 0, s, x, x_scale, router_w,
+                                   bias, ids, w, p, c.H);
+            else
+                hipLaunchKernelGGL((router_few_experts_kernel<true, 1>), fgrid, dim3(256), 0, s, x, x_scale, router_w,
+                                   bias, ids, w, p, c.H);
+        } else {
+            if (split)
+                hipLaunchKernelGGL((router_few_experts_kernel<false, 4>), fgrid, dim3(256), 0, s, x, x_scale, router_w,
+                                   bias, ids, w, p, c.H);
+            else
+                hipLaunchKernelGGL((router_few_experts_kernel<false, 1>), fgrid, dim3(256), 0, s, x, x_scale, router_w,
+                                   bias, ids, w, p, c.H);
+        }
         return check_launch();
     }
     float *zpart = static_cast<float *>(ws);

@@ -47,6 +47,9 @@ CASES = {
     "qx_small": syn.Workload("qx_small", T=150, H=256, I=256, E=8, top_k=2, fp8=True, quantize_x=True),
     "qx_grouped_local": syn.Workload("qx_grouped_local", T=530, H=384, I=128, E=64, top_k=6, n_group=4, topk_group=3,
                                      fp8=True, quantize_x=True, local_offset=16, local_experts=32, **GROUPED),
+    # few experts and few tokens: the one-launch router splits H over four wavefronts per token
+    "few_split": syn.Workload("few_split", T=37, H=1024, I=64, E=8, top_k=2),
+    "few_split_fp8": syn.Workload("few_split_fp8", T=21, H=1152, I=128, E=12, top_k=3, fp8=True, **GROUPED),
     # the limits of the interface: 512 experts (8 per lane in the router) and 64 experts per token
     "max_experts": syn.Workload("max_experts", T=40, H=128, I=64, E=512, top_k=64),
 }
@@ -195,6 +198,25 @@ def test_quantize_act_is_bit_exact(T, H, scale):
     q_ref, s_ref = orc.quantize_rows_1x128(x)
     assert np.array_equal(xs.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
     assert np.array_equal(xq.cpu().view(torch.uint8).numpy(), q_ref)
+
+
+def test_local_share_without_any_pair():
+    """A device whose experts nobody chose: empty schedule, both GEMMs launch with nothing to do,
+    and the combine writes exact zeros."""
+    wl = syn.Workload("nolocal", T=40, H=256, I=128, E=16, top_k=2, local_offset=12, local_experts=4)
+    cfg = moe.MoEConfig.from_workload(wl)
+    gpu = syn.make_inputs(wl, seed=3).to("cuda")
+    rng = np.random.default_rng(3)
+    ids = rng.integers(0, 12, size=(wl.T, wl.top_k)).astype(np.int32)        # experts 0..11 only
+    off, sp, inv, tiles, sched = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
+    act, _ = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, None, gpu.w1, None, sp, tiles, sched)
+    y = moe.moe_grouped_gemm_down(cfg, act, None, gpu.w2, None, tiles, sched)
+    w = torch.rand((wl.T, wl.top_k), device="cuda")
+    out = moe.moe_combine(cfg, y, w, inv)
+    torch.cuda.synchronize()
+    assert off.cpu().tolist() == [0] * 5 and sched.cpu().tolist()[:10] == [0] * 10
+    assert (inv.cpu().numpy() == -1).all()
+    assert not out.view(torch.int16).cpu().numpy().any()
 
 
 def test_forward_zero_tokens_and_errors():
