@@ -83,6 +83,9 @@ def main():
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, used to scale "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--graph", action="store_true",
+                    help="supplementary: also time the same forward replayed from a HIP graph (the five launches "
+                         "recorded once; reported as graph_replay_us, never as value)")
     ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
                     help="CPU work budget for the oracle sample; 0 skips the CPU baseline")
     args = ap.parse_args()
@@ -129,6 +132,30 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
+
+    # supplementary: the same call recorded into a HIP graph and replayed (launch overhead of the
+    # multi-launch pipeline removed; the library neither allocates nor synchronises, so it can be captured)
+    graph_us = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            call()                                       # everything one-time happens outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            call()
+        ref_out = out.clone()
+        for _ in range(W):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - g0) * 1e6 / K
+        assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16)), "graph replay changed the output"
 
     step_ms = {name: 0.0 for name in moe.STEP_NAMES}
     for ev in events:
@@ -210,6 +237,7 @@ def main():
         "gbps": round(gbps, 1), "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
         "roofline_time_us": round(max(flops / (PEAK_MFMA_TFLOPS[kind] * 1e12), bytes_min / (PEAK_HBM_GBPS * 1e9)) * 1e6, 1),
         "gpu_event_us": round(gpu_ms * 1e3, 2),
+        "graph_replay_us": None if graph_us is None else round(graph_us, 2),
         "step_us": {n_: round(v * 1e3, 2) for n_, v in step_ms.items()},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_sample": parity,
     }
