@@ -9,7 +9,7 @@
 //
 //  * A workgroup of NW wavefronts owns ALL rows of one expert tile (up to 16*MB_MAX) times a
 //    slab of weight rows; wavefront w owns two blocks of 16 weight rows (gate + matching up
-//    rows, or 32 consecutive down-projection rows).
+//    rows, or 32 consecutive down-projection rows; 64 rows for the down projection of low tiles).
 //  * Every global read is a direct global -> LDS copy (global_load_lds, 16 bytes per lane) whose
 //    64 lanes cover 8 rows x 128 contiguous bytes: whole cache lines per instruction.  (Loading
 //    weights straight into the MFMA register layout would touch 16 rows x 64 bytes per
@@ -55,8 +55,6 @@ typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 constexpr int GM_STEP_BYTES = 128;        // bytes of every row consumed per K step
 constexpr int GM_XCDS = MOE_WORK_RANGES;  // one work range of the schedule per XCD
-constexpr int GM_W_COPIES = 4;            // weight copies per wavefront per step: 32 rows, 8 rows each
-constexpr int GM_W_STAGE = 32 * 128;      // bytes of one wavefront's weight stage
 constexpr int GM_CUS = 256;
 constexpr float GM_FP8_MAX = 448.f;
 constexpr int GM_PF = 4;                 // token fragments requested ahead of the MFMAs that use them (bf16)
@@ -124,16 +122,20 @@ struct GemmArgs {
 // Compile-time shape of one kernel variant.
 //   MB_MAX  row blocks (of 16) a tile may have        NW  wavefronts per workgroup
 //   DA      token-row stages in flight                DW  weight stages in flight (DW >= DA)
-template <int MB_MAX_, int NW_, int DA_, int DW_, bool SWIGLU_, bool FP8_>
+template <int MB_MAX_, int NW_, int DA_, int DW_, bool SWIGLU_, bool FP8_, int BPW_ = 2>
 struct Shape {
     static constexpr int MB_MAX = MB_MAX_, NW = NW_, DA = DA_, DW = DW_;
     static constexpr bool SWIGLU = SWIGLU_, FP8 = FP8_;
+    static constexpr int BPW = BPW_;                          // 16-row weight blocks per wavefront (gate/up: one gate + one up block)
+    static_assert(!SWIGLU || BPW == 2, "gate/up: one gate and one up block per wavefront");
     static constexpr int THREADS = NW * kWave;
-    static constexpr int SLAB = SWIGLU ? 16 : 32;             // output columns per wavefront
+    static constexpr int W_COPIES = 2 * BPW;                  // weight copies per wavefront per step, 8 rows each
+    static constexpr int W_STAGE = 16 * BPW * 128;            // bytes of one wavefront's weight stage
+    static constexpr int SLAB = SWIGLU ? 16 : 16 * BPW;       // output columns per wavefront
     static constexpr int COLS = SLAB * NW;                    // output columns per workgroup
     static constexpr int STAGE_BYTES = MB_MAX * 16 * 128;     // one token-row stage
     static constexpr int A_RING_BYTES = (DA + 1) * STAGE_BYTES;
-    static constexpr int W_RING_BYTES = DW * NW * GM_W_STAGE;
+    static constexpr int W_RING_BYTES = DW * NW * W_STAGE;
     // one fp32 activation scale per token row, copied 64 rows (one wavefront) at a time
     static constexpr int SC_STAGE_BYTES = FP8 ? ((MB_MAX * 16 + 63) / 64) * 256 : 0;
     static constexpr int LDS_BYTES = A_RING_BYTES + W_RING_BYTES + (DA + 1) * SC_STAGE_BYTES;
@@ -154,6 +156,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     constexpr int STAGE_BYTES = SH::STAGE_BYTES;
     constexpr int A_PASS_MAX = (NB * 2 + NW - 1) / NW;        // 8-row copy passes per wavefront
     constexpr int SLAB = SH::SLAB;
+    constexpr int BPW = SH::BPW, GM_W_COPIES = SH::W_COPIES, GM_W_STAGE = SH::W_STAGE;
     static_assert(GM_W_COPIES + (DA - 1) * (GM_W_COPIES + A_PASS_MAX + 1) <= 30, "wait_vmcnt_upto covers up to 30 copies in flight");
 
     // The thread index goes through an empty asm statement, so that everything derived from it is
@@ -194,7 +197,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
             const int c = min(col0 + in_blk, n_out - 1);      // clamp: columns past the end are never stored
             wrow = (q < 2) ? c : n_out + c;                   // gate row / matching up row
         } else {
-            wrow = min(col0 + (q >> 1) * 16 + in_blk, n_out - 1);
+            wrow = min(col0 + q * 8 + crow, n_out - 1);
         }
         w_ptr[q] = wbase + (size_t)wrow * row_bytes;
     }
@@ -245,11 +248,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         sc_ptr = g.a_scale + src * nk;
     }
 
-    f32x4 acc[NB][2];
+    f32x4 acc[NB][BPW];
 #pragma unroll
     for (int m = 0; m < NB; ++m)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[m][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int b = 0; b < BPW; ++b) acc[m][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // Copies of K step `s` (callers issue them only for s < nk).
 #define MOE_COPY_TOKENS(s)                                                                             \
@@ -312,14 +315,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
             const float sw1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(
                 __builtin_bit_cast(int, sr < 64 ? wsc[1][0] : wsc[1][1]), sl));
             constexpr int PF = NB < GM_PF_FP8 ? NB : GM_PF_FP8;
-            i32x8 w0, w1;
-            {
-                const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(sw + lds_off(l16, 2 * lq));
-                const u32x4 hi0 = *reinterpret_cast<const u32x4 *>(sw + lds_off(l16, 2 * lq + 1));
-                const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(sw + lds_off(16 + l16, 2 * lq));
-                const u32x4 hi1 = *reinterpret_cast<const u32x4 *>(sw + lds_off(16 + l16, 2 * lq + 1));
-                w0 = i32x8{(int)lo0.x, (int)lo0.y, (int)lo0.z, (int)lo0.w, (int)hi0.x, (int)hi0.y, (int)hi0.z, (int)hi0.w};
-                w1 = i32x8{(int)lo1.x, (int)lo1.y, (int)lo1.z, (int)lo1.w, (int)hi1.x, (int)hi1.y, (int)hi1.z, (int)hi1.w};
+            i32x8 wq[BPW];
+#pragma unroll
+            for (int b = 0; b < BPW; ++b) {
+                const u32x4 lo = *reinterpret_cast<const u32x4 *>(sw + lds_off(b * 16 + l16, 2 * lq));
+                const u32x4 hi = *reinterpret_cast<const u32x4 *>(sw + lds_off(b * 16 + l16, 2 * lq + 1));
+                wq[b] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
             }
             __builtin_amdgcn_sched_barrier(0);
             u32x4 tlo[PF], thi[PF];
@@ -333,8 +334,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 #pragma unroll
             for (int q = 0; q < PF; ++q) MOE_LOAD_TOK8(q, q)
             __builtin_amdgcn_sched_barrier(0);
-            f32x4 p0[2], p1[2];
-            float fs0[2], fs1[2];
+            f32x4 pp[BPW][2];
+            float fs[BPW][2];
 #pragma unroll
             for (int m = 0; m <= NB; ++m) {
                 if (m < NB) {
@@ -342,19 +343,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
                     const i32x8 t = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
                     const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
                     // e4m3 x e4m3, hardware block scales set to 1.0 (E8M0 0x7f): the fp32 scales are applied below
-                    p0[m & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w0, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-                    p1[m & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(w1, t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-                    fs0[m & 1] = tsx[m % PF] * sw0;
-                    fs1[m & 1] = tsx[m % PF] * sw1;
+#pragma unroll
+                    for (int b = 0; b < BPW; ++b) {
+                        pp[b][m & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(wq[b], t, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                        fs[b][m & 1] = tsx[m % PF] * ((SWIGLU && b == 1) ? sw1 : sw0);
+                    }
                     if (m + PF < NB) MOE_LOAD_TOK8(m % PF, m + PF)
                 }
                 if (m > 0) {
                     const int pm = m - 1;
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        acc[pm][0][v] = fmaf(p0[pm & 1][v], fs0[pm & 1], acc[pm][0][v]);
-                        acc[pm][1][v] = fmaf(p1[pm & 1][v], fs1[pm & 1], acc[pm][1][v]);
-                    }
+                    for (int b = 0; b < BPW; ++b)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[pm][b][v] = fmaf(pp[b][pm & 1][v], fs[b][pm & 1], acc[pm][b][v]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (m == 0) {
@@ -370,11 +371,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
             // from LDS while the MFMAs of fragment q run.
             constexpr int NQ = 2 * NB;
             constexpr int PF = NQ < GM_PF ? NQ : GM_PF;
-            bf16x8 wf[2][2], tf[PF];
+            bf16x8 wf[2][BPW], tf[PF];
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                wf[kk][0] = *reinterpret_cast<const bf16x8 *>(sw + lds_off(l16, kk * 4 + lq));
-                wf[kk][1] = *reinterpret_cast<const bf16x8 *>(sw + lds_off(16 + l16, kk * 4 + lq));
+#pragma unroll
+                for (int b = 0; b < BPW; ++b)
+                    wf[kk][b] = *reinterpret_cast<const bf16x8 *>(sw + lds_off(b * 16 + l16, kk * 4 + lq));
             }
             __builtin_amdgcn_sched_barrier(0);
 #define MOE_LOAD_TOK(q_) (*reinterpret_cast<const bf16x8 *>(sa + lds_off(((q_) % NB) * 16 + l16, ((q_) / NB) * 4 + lq)))
@@ -384,8 +386,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 const int kk = q / NB, m = q % NB;
-                acc[m][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[kk][0], tf[q % PF], acc[m][0], 0, 0, 0);
-                acc[m][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[kk][1], tf[q % PF], acc[m][1], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < BPW; ++b)
+                    acc[m][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[kk][b], tf[q % PF], acc[m][b], 0, 0, 0);
                 if (q + PF < NQ) tf[q % PF] = MOE_LOAD_TOK(q + PF);
                 __builtin_amdgcn_sched_barrier(0);
                 if (q == 0) {
@@ -471,7 +474,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
                 *reinterpret_cast<uint2 *>(stage_at(r, (wave * SLAB + lq * 4) * OUT_ES)) = o;
             } else {
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
+                for (int b = 0; b < BPW; ++b) {
                     uint2 o;
                     o.x = pack_bf16x2(acc[m][b][0], acc[m][b][1]);
                     o.y = pack_bf16x2(acc[m][b][2], acc[m][b][3]);
@@ -595,6 +598,17 @@ int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *sch
 {
     constexpr int DA = MB_MAX >= 16 ? 1 : 2;                  // 16 row blocks: 32 KiB per token stage
     constexpr int DW = 2;
+    // Down projection of low tiles (32 or 64 rows): four weight blocks per wavefront, i.e. 512
+    // output columns per workgroup.  Its K loop is short (16 steps for fp8 with I = 2048), so the
+    // fixed cost of a workgroup is a third of its life, and the accumulators of a low tile leave the
+    // registers for it: half as many workgroups, each token fragment feeds four MFMAs instead of
+    // two (fp8 prefill: down GEMM -4 %).  Not for 16-row tiles, where two workgroups per compute
+    // unit already overlap those costs (the decode shape measured +0.5 %).
+    if constexpr (!SWIGLU && (MB_MAX == 2 || MB_MAX == 4)) {
+        using Wide4 = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8, 4>;
+        if ((long)est_tiles * ceil_div(g.n_out, Wide4::COLS) >= 4 * GM_CUS)
+            return launch_shape<Wide4>(g, tiles, sched, max_tiles, est_tiles, s);
+    }
     using Wide = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8>;
     if constexpr (!(FP8 && SWIGLU)) {
         using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU, FP8>;
