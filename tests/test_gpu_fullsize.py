@@ -47,12 +47,12 @@ def _check_workload(gpu, host_w, sample_tokens=SAMPLE_TOKENS):
     ids_g, w_g = moe.moe_route(cfg, gpu.x, gpu.x_scale, gpu.router_w, gpu.bias)
     other, swapped, same_set = compare_routing(ids_g, w_g, ids_r, w_r, margin, wl.routed_scale, wl.E,
                                                choice_keys(p, z))
-    off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_g)
+    off_g, sp_g, inv_g, tiles, sched = moe.moe_permute(cfg, ids_g)
     torch.cuda.synchronize()
     off_r, sp_r, inv_r, kept = local_permute(ids_g.cpu().numpy(), wl.E, wl.local_offset, wl.local_experts)   # oracle on the GPU's own routing
     assert np.array_equal(off_g.cpu().numpy(), off_r)
     assert np.array_equal(sp_g.cpu().numpy()[:kept], sp_r) and np.array_equal(inv_g.cpu().numpy(), inv_r)
-    check_tiles(tiles, ntiles, off_r, moe.moe_tile_rows(cfg))
+    check_tiles(tiles, sched, off_r, moe.moe_tile_rows(cfg))
     load = np.diff(off_r)
     print(f"  routing: tie-excused tokens={other} swapped slots={swapped} of {wl.T}; "
           f"active experts={(load > 0).sum()} max/mean load={load.max() / load.mean():.2f}", flush=True)

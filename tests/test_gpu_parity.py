@@ -82,12 +82,12 @@ def test_permute(case):
     wl, cpu, gpu, (p, ids, w, margin, offsets, sorted_pair, inv, _k) = case
     cfg = moe.MoEConfig.from_workload(wl)
     ids_d = torch.from_numpy(ids).cuda()
-    off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_d)
+    off_g, sp_g, inv_g, tiles, sched = moe.moe_permute(cfg, ids_d)
     torch.cuda.synchronize()
     assert np.array_equal(off_g.cpu().numpy(), offsets)
     assert np.array_equal(sp_g.cpu().numpy()[: len(sorted_pair)], sorted_pair)      # rows of the kept pairs
     assert np.array_equal(inv_g.cpu().numpy(), inv)
-    n = check_tiles(tiles, ntiles, offsets, moe.moe_tile_rows(cfg))
+    n = check_tiles(tiles, sched, offsets, moe.moe_tile_rows(cfg))
     assert n <= moe.moe_max_tiles(cfg)
 
 
@@ -95,10 +95,10 @@ def _staged(case):
     wl, cpu, gpu, (p, ids, w, margin, offsets, sorted_pair, inv, _k) = case
     cfg = moe.MoEConfig.from_workload(wl)
     ids_d = torch.from_numpy(ids).cuda()
-    off_g, sp_g, inv_g, tiles, ntiles = moe.moe_permute(cfg, ids_d)
+    off_g, sp_g, inv_g, tiles, sched = moe.moe_permute(cfg, ids_d)
     tok = sorted_pair // wl.top_k                            # one entry per kept pair, in sorted-row order
     exp = ids.reshape(-1)[sorted_pair] - wl.local_offset     # index into the (local) weight arrays
-    return wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv
+    return wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, sched, tok, exp, inv
 
 
 def _gemm_x(gpu, p):
@@ -119,8 +119,8 @@ def _act_f64(act, scale):
 
 
 def test_gemm_swiglu(case):
-    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
-    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, *_gemm_x(gpu, p), gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
+    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, sched, tok, exp, inv = _staged(case)
+    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, *_gemm_x(gpu, p), gpu.w1, gpu.w1_scale, sp_g, tiles, sched)
     torch.cuda.synchronize()
     ref = orc.swiglu_rows(p, tok, exp)
     n = len(tok)                                             # rows beyond the kept pairs are never written
@@ -139,9 +139,9 @@ def test_gemm_swiglu(case):
 
 
 def test_gemm_down(case):
-    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
-    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, *_gemm_x(gpu, p), gpu.w1, gpu.w1_scale, sp_g, tiles, ntiles)
-    y_g = moe.moe_grouped_gemm_down(cfg, act_g, sc_g, gpu.w2, gpu.w2_scale, tiles, ntiles)
+    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, sched, tok, exp, inv = _staged(case)
+    act_g, sc_g = moe.moe_grouped_gemm_swiglu(cfg, *_gemm_x(gpu, p), gpu.w1, gpu.w1_scale, sp_g, tiles, sched)
+    y_g = moe.moe_grouped_gemm_down(cfg, act_g, sc_g, gpu.w2, gpu.w2_scale, tiles, sched)
     torch.cuda.synchronize()
     n = len(tok)
     ref = orc.down_rows(p, exp, _act_f64(act_g[:n], None if sc_g is None else sc_g[:n]))   # from the very activations the GPU consumed
@@ -151,7 +151,7 @@ def test_gemm_down(case):
 
 
 def test_combine(case):
-    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, ntiles, tok, exp, inv = _staged(case)
+    wl, cfg, gpu, p, ids, w, sp_g, inv_g, tiles, sched, tok, exp, inv = _staged(case)
     g = torch.Generator().manual_seed(1)
     y = torch.randn((cfg.P, wl.H), generator=g).bfloat16()
     w32 = torch.from_numpy(w.astype(np.float32))
@@ -227,9 +227,9 @@ def test_forward_zero_tokens_and_errors():
     wl = syn.Workload("empty", T=0, H=128, I=64, E=8, top_k=2)
     cfg = moe.MoEConfig.from_workload(wl)
     ids = torch.empty((0, 2), dtype=torch.int32, device="cuda")
-    off, sp, inv, tiles, ntiles = moe.moe_permute(cfg, ids)
+    off, sp, inv, tiles, sched = moe.moe_permute(cfg, ids)
     torch.cuda.synchronize()
-    assert off.cpu().tolist() == [0] * 9 and ntiles.cpu().tolist()[:10] == [0] * 10
+    assert off.cpu().tolist() == [0] * 9 and sched.cpu().tolist()[:10] == [0] * 10
     # workspace one byte short is refused before anything is enqueued
     wl = syn.WORKLOADS["tiny"]
     gpu = syn.make_inputs(wl, seed=0).to("cuda")
@@ -246,7 +246,7 @@ def test_permute_drops_out_of_range_ids_and_handles_one_hot_expert():
     ids = rng.integers(0, 8, size=(50, 2)).astype(np.int32)
     ids[::7, 1] = -1
     ids[3::11, 0] = 8
-    off, sp, inv, tiles, ntiles = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
+    off, sp, inv, tiles, sched = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
     torch.cuda.synchronize()
     flat = ids.reshape(-1)
     keep = (flat >= 0) & (flat < 8)
@@ -258,11 +258,11 @@ def test_permute_drops_out_of_range_ids_and_handles_one_hot_expert():
     assert (inv_g[~keep] == -1).all() and np.array_equal(inv_g[keep], inv_r)
     # every pair on one expert: maximum rows for a single segment
     ids = np.full((50, 2), 5, dtype=np.int32)
-    off, sp, inv, tiles, ntiles = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
+    off, sp, inv, tiles, sched = moe.moe_permute(cfg, torch.from_numpy(ids).cuda())
     torch.cuda.synchronize()
     off_r, sp_r, inv_r = orc.permute(ids, 8)
     assert np.array_equal(off.cpu().numpy(), off_r) and np.array_equal(sp.cpu().numpy(), sp_r)
-    check_tiles(tiles, ntiles, off_r, moe.moe_tile_rows(cfg))
+    check_tiles(tiles, sched, off_r, moe.moe_tile_rows(cfg))
 
 
 @pytest.mark.parametrize("T, k, E, lo, n", [(2500, 8, 256, 0, 0), (3001, 6, 64, 16, 24), (9000, 8, 512, 0, 0),
