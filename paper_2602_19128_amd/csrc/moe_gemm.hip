@@ -141,12 +141,15 @@ struct Shape {
     static constexpr int LDS_BYTES = A_RING_BYTES + W_RING_BYTES + (DA + 1) * SC_STAGE_BYTES;
     static_assert(DW >= DA && DA >= 1, "weights are copied at least as far ahead as token rows");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
+    // half-width items (see gemm_tile): wide workgroups only; the fp8 gate/up epilogue needs whole 128-column blocks
+    static constexpr bool HALF_ITEMS = NW >= 8 && !(FP8 && SWIGLU);
     static_assert(!(FP8 && SWIGLU) || COLS == kQBlock, "fp8 gate/up: a workgroup re-quantises one 1x128 block per row");
 };
 
 // Everything after the (tile, column slab) decision, instantiated per active row-block count NB.
 template <class SH, int NB>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, int work, unsigned char *smem)
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, int half, int work,
+                                          unsigned char *smem)
 {
     constexpr int NW = SH::NW, DA = SH::DA, DW = SH::DW;
     constexpr bool SWIGLU = SH::SWIGLU, FP8 = SH::FP8;
@@ -185,7 +188,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 
     // ---- weight row pointers: copy q (0..3) moves rows 8q..8q+7 of this wavefront's 32 rows
     // (rows 0..15 = first block, 16..31 = second block)
-    const int col0 = ct * SH::COLS + wave * SLAB;             // first output column of this wavefront
+    // half = 0: the whole column slab.  half = 1 / 2: its first / second half only, computed by the
+    // first half of the wavefronts (the others still copy token rows and keep the barriers); such
+    // items fill the compute units that the last round of a launch would leave idle, and with
+    // half the fragment traffic through LDS their K steps are shorter.
+    const bool active = !SH::HALF_ITEMS || half == 0 || wave < NW / 2;
+    const int half_col = (SH::HALF_ITEMS && half == 2) ? SH::COLS / 2 : 0;
+    const int col0 = ct * SH::COLS + half_col + ((SH::HALF_ITEMS && half) ? wave % (NW / 2) : wave) * SLAB;   // first output column of this wavefront
+    const int wc = active ? GM_W_COPIES : 0;                  // weight copies this wavefront issues per step
     const int w_rows = SWIGLU ? 2 * n_out : n_out;
     const unsigned char *wbase = g.W + (size_t)tile.expert * w_rows * row_bytes + cbyte;
     const unsigned char *w_ptr[GM_W_COPIES];
@@ -286,7 +296,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 #pragma unroll
     for (int t = -DW; t < 0; ++t) {
         if (t + DA >= 0 && t + DA < nk) MOE_COPY_TOKENS(t + DA)
-        if (t + DW < nk) MOE_COPY_WEIGHTS(t + DW)
+        if (active && t + DW < nk) MOE_COPY_WEIGHTS(t + DW)
     }
 
     for (int s = 0; s < nk; ++s) {
@@ -295,16 +305,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         // younger of the two stay in flight: the weight copy sharing the slot of that token copy
         // (when the weights run further ahead than the token rows) and the DA-1 slots after it.
         // Near the end of K some of those copies do not exist; they are not counted.
-        int in_flight = (DW > DA && s - DA + DW < nk) ? GM_W_COPIES : 0;
+        int in_flight = (DW > DA && s - DA + DW < nk) ? wc : 0;
 #pragma unroll
         for (int t = 1 - DA; t < 0; ++t)
-            in_flight += (s + t + DA < nk ? a_cnt : 0) + (s + t + DW < nk ? GM_W_COPIES : 0);
+            in_flight += (s + t + DA < nk ? a_cnt : 0) + (s + t + DW < nk ? wc : 0);
         wait_vmcnt_upto(in_flight);
         asm volatile("s_barrier" ::: "memory");               // token stage s complete for everyone; stage s-1 free
         if (s + DA < nk) MOE_COPY_TOKENS(s + DA)
         __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sa = smem + (s % SA) * STAGE_BYTES;
         const unsigned char *sw = w_ring + (s % SW) * GM_W_STAGE;
+        if (active) {
         if constexpr (FP8) {
             // one MFMA spans the whole step: lane (l16, lq) holds bytes 32*lq .. 32*lq+31 of its row
             const float *ssc = reinterpret_cast<const float *>(sc_ring + (s % SA) * SH::SC_STAGE_BYTES);
@@ -400,6 +411,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
             }
 #undef MOE_LOAD_TOK
         }
+        }   // active
         __builtin_amdgcn_sched_barrier(0);
     }
     MOE_WAIT_VMCNT(0);                                        // nothing is in flight any more; cheap insurance for the LDS reuse below
@@ -422,6 +434,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         return stage + r * ROW_B + ((((byte >> 4) ^ ((r & (CPR / 2 - 1)) << 1))) << 4) + (byte & 15);
     };
     __syncthreads();                                          // every wavefront is done with the rings
+    const int scol = ((SH::HALF_ITEMS && half) ? wave % (NW / 2) : wave) * SLAB;   // this wavefront's first column inside the staged tile
     if constexpr (SWIGLU && FP8) {
         // act = silu(g)*u, then per-row amax over the workgroup's 128 columns -> scale = amax/448
         float a[NB][4];
@@ -454,10 +467,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
             int packed = 0;
             packed = __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], packed, false);
             packed = __builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], packed, true);
-            *reinterpret_cast<int *>(stage_at(r, (wave * SLAB + lq * 4) * OUT_ES)) = packed;
+            *reinterpret_cast<int *>(stage_at(r, (scol + lq * 4) * OUT_ES)) = packed;
             if (r < rows && wave == 0 && lq == 0) g.out_scale[(size_t)(tile.row0 + r) * (n_out / kQBlock) + ct] = scale;
         }
-    } else {
+    } else if (active) {
 #pragma unroll
         for (int m = 0; m < NB; ++m) {
             const int r = m * 16 + l16;
@@ -471,14 +484,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
                 uint2 o;
                 o.x = pack_bf16x2(a[0], a[1]);
                 o.y = pack_bf16x2(a[2], a[3]);
-                *reinterpret_cast<uint2 *>(stage_at(r, (wave * SLAB + lq * 4) * OUT_ES)) = o;
+                *reinterpret_cast<uint2 *>(stage_at(r, (scol + lq * 4) * OUT_ES)) = o;
             } else {
 #pragma unroll
                 for (int b = 0; b < BPW; ++b) {
                     uint2 o;
                     o.x = pack_bf16x2(acc[m][b][0], acc[m][b][1]);
                     o.y = pack_bf16x2(acc[m][b][2], acc[m][b][3]);
-                    *reinterpret_cast<uint2 *>(stage_at(r, (wave * SLAB + b * 16 + lq * 4) * OUT_ES)) = o;
+                    *reinterpret_cast<uint2 *>(stage_at(r, (scol + b * 16 + lq * 4) * OUT_ES)) = o;
                 }
             }
         }
@@ -486,9 +499,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     __syncthreads();
     // row-major write-out: consecutive lanes hold consecutive 16-byte chunks of a row
     const size_t out_pitch = (size_t)n_out * OUT_ES;
-    for (int c = tid; c < rows * CPR; c += SH::THREADS) {
-        const int r = c / CPR, ch = c % CPR;
-        const int col = ct * SH::COLS + ch * (16 / OUT_ES);   // n_out is a multiple of 16 elements: chunks are all in or all out
+    const int cpr = (SH::HALF_ITEMS && half) ? CPR / 2 : CPR;                     // chunks of a row that were computed
+    for (int c = tid; c < rows * cpr; c += SH::THREADS) {
+        const int r = c / cpr, ch = c % cpr;
+        const int col = ct * SH::COLS + half_col + ch * (16 / OUT_ES);   // n_out is a multiple of 16 elements: chunks are all in or all out
         if (col < n_out) {
             const u32x4 v = *reinterpret_cast<const u32x4 *>(stage_at(r, ch * 16));
             u32x4 *dst = reinterpret_cast<u32x4 *>(g.out + (size_t)(tile.row0 + r) * out_pitch + (size_t)col * OUT_ES);
@@ -499,15 +513,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 }
 
 template <class SH, int NB>
-__device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const moe_tile &tile, int ct, int work,
-                                                unsigned char *smem)
+__device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const moe_tile &tile, int ct, int half,
+                                                int work, unsigned char *smem)
 {
     if constexpr (NB > SH::MB_MAX) {
         return;
     } else {
         constexpr int NEXT = NB + 1;
-        if (nb <= NB) gemm_tile<SH, NB>(g, tile, ct, work, smem);
-        else dispatch_blocks<SH, NEXT>(nb, g, tile, ct, work, smem);
+        if (nb <= NB) gemm_tile<SH, NB>(g, tile, ct, half, work, smem);
+        else dispatch_blocks<SH, NEXT>(nb, g, tile, ct, half, work, smem);
     }
 }
 
@@ -526,7 +540,7 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
 template <class SH>
 __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
                                                                    const int32_t *__restrict__ sched, int col_tiles,
-                                                                   int whole_ranges)
+                                                                   int whole_ranges, int round_slots)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int part = blockIdx.x % MOE_WORK_RANGES;
@@ -550,7 +564,11 @@ __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, c
     // tallest tile of the list (its first record) has more than 128 rows.
     const bool zigzag = !whole_ranges && (SH::SWIGLU || tiles[0].rows > 128);
     const int nchunks = ceil_div(items, col_tiles);
-    const int slots = zigzag ? nchunks * col_tiles : items;
+    // A last round that would fill at most half of the XCD's workgroup slots is handed out as
+    // half-width items, two per column slab.
+    const int rest = items % round_slots;
+    const int halved = (SH::HALF_ITEMS && whole_ranges && rest > 0 && 2 * rest <= round_slots) ? rest : 0;
+    const int slots = zigzag ? nchunks * col_tiles : items + halved;
     for (int slot = blockIdx.x / MOE_WORK_RANGES; slot < slots; slot += stride) {
         int pos = slot;
         if (zigzag) {
@@ -559,13 +577,19 @@ __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, c
             pos = pc * col_tiles + slot % col_tiles;
             if (pos >= items) continue;                        // the part's last chunk may be short
         }
+        int half = 0;
+        if (pos >= items - halved) {                           // (never together with zigzag)
+            const int h = pos - (items - halved);
+            pos = items - halved + (h >> 1);
+            half = 1 + (h & 1);
+        }
         const int work = first + pos;
         const moe_tile head = tiles[work / col_tiles];
         const int local = work - head.first * col_tiles;       // index inside this expert's work
         const int ct = local / head.count;                     // column slab
         const moe_tile tile = tiles[head.first + local % head.count];
         const int nb = ceil_div(tile.rows, 16);
-        dispatch_blocks<SH, 1>(nb, g, tile, ct, work, smem);
+        dispatch_blocks<SH, 1>(nb, g, tile, ct, half, work, smem);
         __syncthreads();                                       // the output tile has left LDS
     }
 }
@@ -575,18 +599,22 @@ int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
                  hipStream_t s)
 {
     const int col_tiles = ceil_div(g.n_out, SH::COLS);
-    // a part holds about an eighth of the tiles; a little slack keeps the loop in the kernel at one trip
-    const int blocks = (ceil_div(max_tiles, GM_XCDS) + 1) * col_tiles * GM_XCDS;
     auto kern = grouped_gemm_kernel<SH>;
-    static bool attr_done = false;          // raise the dynamic-LDS limit once per variant
-    if (!attr_done) {
+    static int round_slots = 0;             // workgroups one XCD runs at once; set once per variant with the dynamic-LDS limit
+    if (round_slots == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
         if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
-        attr_done = true;
+        // workgroups a compute unit holds at once: LDS (160 KiB) and wavefront slots (32) decide it
+        int per_cu = (160 * 1024) / SH::LDS_BYTES;
+        if (per_cu > 32 / SH::NW) per_cu = 32 / SH::NW;
+        round_slots = (GM_CUS / GM_XCDS) * (per_cu < 1 ? 1 : per_cu);
     }
+    // a part holds about an eighth of the tiles; the slack (a tile's slabs, and the half-width items
+    // of a last round) keeps the loop in the kernel at one trip
+    const int blocks = ((ceil_div(max_tiles, GM_XCDS) + 1) * col_tiles + round_slots / 2) * GM_XCDS;
     const int whole_ranges = est_tiles <= 8 * GM_XCDS ? 1 : 0;   // at most eight tiles per XCD
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, sched, col_tiles, whole_ranges);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, sched, col_tiles, whole_ranges, round_slots);
     return check_launch();
 }
 
