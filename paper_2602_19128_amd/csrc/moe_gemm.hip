@@ -147,7 +147,7 @@ struct Shape {
 };
 
 // Everything after the (tile, column slab) decision, instantiated per active row-block count NB.
-template <class SH, int NB>
+template <class SH, int NB, bool HALF>
 __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, int half, int work,
                                           unsigned char *smem)
 {
@@ -192,9 +192,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     // first half of the wavefronts (the others still copy token rows and keep the barriers); such
     // items fill the compute units that the last round of a launch would leave idle, and with
     // half the fragment traffic through LDS their K steps are shorter.
-    const bool active = !SH::HALF_ITEMS || half == 0 || wave < NW / 2;
-    const int half_col = (SH::HALF_ITEMS && half == 2) ? SH::COLS / 2 : 0;
-    const int col0 = ct * SH::COLS + half_col + ((SH::HALF_ITEMS && half) ? wave % (NW / 2) : wave) * SLAB;   // first output column of this wavefront
+    const bool active = !HALF || wave < NW / 2;               // (HALF is instantiated separately: whole slabs keep their code)
+    const int half_col = (HALF && half == 2) ? SH::COLS / 2 : 0;
+    const int col0 = ct * SH::COLS + half_col + (HALF ? wave % (NW / 2) : wave) * SLAB;   // first output column of this wavefront
     const int wc = active ? GM_W_COPIES : 0;                  // weight copies this wavefront issues per step
     const int w_rows = SWIGLU ? 2 * n_out : n_out;
     const unsigned char *wbase = g.W + (size_t)tile.expert * w_rows * row_bytes + cbyte;
@@ -434,7 +434,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         return stage + r * ROW_B + ((((byte >> 4) ^ ((r & (CPR / 2 - 1)) << 1))) << 4) + (byte & 15);
     };
     __syncthreads();                                          // every wavefront is done with the rings
-    const int scol = ((SH::HALF_ITEMS && half) ? wave % (NW / 2) : wave) * SLAB;   // this wavefront's first column inside the staged tile
+    const int scol = (HALF ? wave % (NW / 2) : wave) * SLAB;   // this wavefront's first column inside the staged tile
     if constexpr (SWIGLU && FP8) {
         // act = silu(g)*u, then per-row amax over the workgroup's 128 columns -> scale = amax/448
         float a[NB][4];
@@ -499,7 +499,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     __syncthreads();
     // row-major write-out: consecutive lanes hold consecutive 16-byte chunks of a row
     const size_t out_pitch = (size_t)n_out * OUT_ES;
-    const int cpr = (SH::HALF_ITEMS && half) ? CPR / 2 : CPR;                     // chunks of a row that were computed
+    const int cpr = HALF ? CPR / 2 : CPR;                     // chunks of a row that were computed
     for (int c = tid; c < rows * cpr; c += SH::THREADS) {
         const int r = c / cpr, ch = c % cpr;
         const int col = ct * SH::COLS + half_col + ch * (16 / OUT_ES);   // n_out is a multiple of 16 elements: chunks are all in or all out
@@ -520,8 +520,16 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
         return;
     } else {
         constexpr int NEXT = NB + 1;
-        if (nb <= NB) gemm_tile<SH, NB>(g, tile, ct, half, work, smem);
-        else dispatch_blocks<SH, NEXT>(nb, g, tile, ct, half, work, smem);
+        if (nb <= NB) {
+            if constexpr (SH::HALF_ITEMS) {
+                if (half) gemm_tile<SH, NB, true>(g, tile, ct, half, work, smem);
+                else gemm_tile<SH, NB, false>(g, tile, ct, half, work, smem);
+            } else {
+                gemm_tile<SH, NB, false>(g, tile, ct, half, work, smem);
+            }
+        } else {
+            dispatch_blocks<SH, NEXT>(nb, g, tile, ct, half, work, smem);
+        }
     }
 }
 
@@ -612,7 +620,7 @@ int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
     }
     // a part holds about an eighth of the tiles; the slack (a tile's slabs, and the half-width items
     // of a last round) keeps the loop in the kernel at one trip
-    const int blocks = ((ceil_div(max_tiles, GM_XCDS) + 1) * col_tiles + round_slots / 2) * GM_XCDS;
+    const int blocks = ((ceil_div(max_tiles, GM_XCDS) + 1) * col_tiles + (SH::HALF_ITEMS ? round_slots / 2 : 0)) * GM_XCDS;
     const int whole_ranges = est_tiles <= 8 * GM_XCDS ? 1 : 0;   // at most eight tiles per XCD
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, sched, col_tiles, whole_ranges, round_slots);
     return check_launch();
