@@ -91,7 +91,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU kernel path only: run with --gpus 1 "
-              "(this library has no multi-GPU code; see DESIGN.md on how the layer would shard)",
+              "(this library has no multi-GPU code; the layer would shard by expert parallelism, one "
+              "local-expert call per device plus a reduce-scatter of the partial outputs)",
               file=sys.stderr)
         sys.exit(2)
 
