@@ -1,4 +1,4 @@
-"""Writes tests/golden/tiny_seed0.json from the CPU oracle alone.
+"""Writes tests/golden/tiny_seed0.json and tests/golden/quantize_seed0.json from the CPU oracle alone.
 
 The paper prints no numeric values for the MoE operator (Sec. 4.5 describes it in
 prose only), so there is no paper-printed fixture; this file freezes what the
@@ -43,6 +43,23 @@ def main():
         json.dump(doc, f)
         f.write("\n")
     print("wrote", path)
+
+    # the 1x128 activation quantiser (paper Sec. 4.3, kernel table: fp8 packing and scaling) on the
+    # tiny workload's bf16 hidden states: every scale, the codes of the first block, a checksum of all
+    q, scale = orc.quantize_rows_1x128(inp.x)
+    qdoc = {
+        "workload": "tiny", "seed": 0,
+        "source": "oracle_quantize_rows_1x128 on paper_2602_19128_amd.synthetic hidden states (CPU generator)",
+        "scale_bits": scale.view(np.uint32).reshape(-1).tolist(),
+        "codes_row0_block0": q[0, :128].tolist(),
+        "code_sum": int(q.astype(np.int64).sum()),
+        "code_weighted_sum": int((q.astype(np.int64) * (np.arange(q.size).reshape(q.shape) % 251 + 1)).sum()),
+    }
+    qpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "quantize_seed0.json")
+    with open(qpath, "w") as f:
+        json.dump(qdoc, f)
+        f.write("\n")
+    print("wrote", qpath)
 
 
 if __name__ == "__main__":
