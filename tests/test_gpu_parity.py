@@ -52,6 +52,7 @@ CASES = {
     "few_split_fp8": syn.Workload("few_split_fp8", T=21, H=1152, I=128, E=12, top_k=3, fp8=True, **GROUPED),
     # low tiles (32 rows) and enough of them that the down GEMM takes four weight blocks per wavefront
     "low_tiles": syn.Workload("low_tiles", T=256, H=2048, I=128, E=256, top_k=8),
+    "low_tiles_ragged": syn.Workload("low_tiles_ragged", T=256, H=1600, I=64, E=256, top_k=8),   # 3 slabs of 512 columns + 64
     "low_tiles_fp8": syn.Workload("low_tiles_fp8", T=250, H=2048, I=128, E=256, top_k=8, n_group=8, topk_group=4,
                                   fp8=True, **GROUPED),
     # the limits of the interface: 512 experts (8 per lane in the router) and 64 experts per token
