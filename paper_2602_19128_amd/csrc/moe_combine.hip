@@ -1,8 +1,9 @@
 // Weighted combine: out[t,:] = sum_j w[t,j] * y[inv[t*k+j],:].
 //
 // Each thread owns 8 consecutive hidden elements of one token and walks the token's
-// k expert rows in slot order, so the fp32 sum has one fixed order and needs no
-// atomics; the result is rounded once to bf16 (nearest-even).
+// k expert rows in slot order (their loads requested eight at a time), so the fp32 sum
+// has one fixed order and needs no atomics; the result is rounded once to bf16
+// (nearest-even).
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -20,16 +21,30 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t *__restrict
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    for (int j = 0; j < k; ++j) {
-        const int row = inv[(size_t)t * k + j];
-        if (row < 0) continue;
-        const float wt = w[(size_t)t * k + j];
-        const uint4 raw = *reinterpret_cast<const uint4 *>(y + (size_t)row * H + h);
-        const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
+    // slots in groups of CB: the rows of a group are requested together, then added in slot order
+    constexpr int CB = 8;
+    for (int j0 = 0; j0 < k; j0 += CB) {
+        int row[CB];
+        float wt[CB];
+        uint4 raw[CB];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc[2 * i] = fmaf(wt, bf16_bits_to_f32(v[i] & 0xffffu), acc[2 * i]);
-            acc[2 * i + 1] = fmaf(wt, bf16_bits_to_f32(v[i] >> 16), acc[2 * i + 1]);
+        for (int u = 0; u < CB; ++u) {
+            const bool in = j0 + u < k;
+            row[u] = in ? inv[(size_t)t * k + j0 + u] : -1;
+            wt[u] = in ? w[(size_t)t * k + j0 + u] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < CB; ++u)
+            raw[u] = row[u] >= 0 ? *reinterpret_cast<const uint4 *>(y + (size_t)row[u] * H + h) : uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < CB; ++u) {
+            if (row[u] < 0) continue;                      // a pair without a row (its expert is held elsewhere)
+            const uint32_t v[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[2 * i] = fmaf(wt[u], bf16_bits_to_f32(v[i] & 0xffffu), acc[2 * i]);
+                acc[2 * i + 1] = fmaf(wt[u], bf16_bits_to_f32(v[i] >> 16), acc[2 * i + 1]);
+            }
         }
     }
     uint4 o;
