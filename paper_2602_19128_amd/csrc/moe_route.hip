@@ -143,18 +143,21 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const void *__restri
 
 // ---- many tokens: logits on the matrix cores ---------------------------------------------------
 //
-// The fp32 router weights are split once per call into three bf16 planes, w = hi + mid + lo
-// (each the bf16 rounding of what the previous ones leave; together they carry the 24-bit
-// mantissa), so that x . w = x.hi + x.mid + x.lo with bf16 MFMAs: the hidden states are bf16 (or
-// fp8 payloads, exact in bf16), every product is exact in fp32 and the sums accumulate in fp32,
-// which keeps the logits at fp32 accuracy - a routing decision is only allowed to differ from an
-// exact evaluation when its margin is below 1e-6.
+// Each fp32 router weight is split into three bf16 planes, w = hi + mid + lo (each the bf16
+// rounding of what the previous ones leave; together they carry the 24-bit mantissa), so that
+// x . w = x.hi + x.mid + x.lo with bf16 MFMAs: the hidden states are bf16 (or fp8 payloads, exact
+// in bf16), every product is exact in fp32 and the sums accumulate in fp32, which keeps the logits
+// at fp32 accuracy - a routing decision is only allowed to differ from an exact evaluation when
+// its margin is below 1e-6.  The split happens in registers, on the fragment a wavefront has just
+// loaded (a dozen VALU operations per pair of weights, hidden behind the MFMAs): the weights are
+// read as fp32, 4 bytes per element instead of the 6 of stored planes, and no separate pass runs.
 //
 // A workgroup of 8 wavefronts owns TB*16 tokens x 256 experts x one slice of H.  Wavefront w owns
 // expert blocks 2w, 2w+1 (16 experts each) against all token blocks; per 32-wide K step the
-// workgroup stages the token rows and the three weight planes in LDS (double buffered, loads of
-// the next step in registers while the MFMAs of the current one run).  fp8 inputs: the payload is
-// multiplied as is and each 128-wide block's sum is folded in with the token's block scale.
+// workgroup stages the token rows in LDS (double buffered) while every wavefront loads the weights
+// of its own experts straight into registers, both several steps ahead.  fp8 inputs: the payload
+// is multiplied as is and each 128-wide block's sum is folded in with the token's block scale.
+// The partial logits leave through LDS as whole 1 KiB rows.
 typedef __attribute__((ext_vector_type(8))) __bf16 rt_bf16x8;
 typedef __attribute__((ext_vector_type(4))) float rt_f32x4;
 
@@ -163,90 +166,98 @@ constexpr int RM_BK = 32;                  // hidden elements per K step (one MF
 constexpr int RM_THREADS = 512;
 constexpr int RM_MIN_TOKENS = 512;         // below this the FMA kernel's finer tiles fill the chip better
 
-__global__ __launch_bounds__(256) void router_split_weights_kernel(const float *__restrict__ w, uint16_t *__restrict__ planes,
-                                                                   size_t n)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const float v = w[i];
-    const uint32_t hi = f32_to_bf16_bits(v);
-    const float r1 = v - bf16_bits_to_f32(hi);
-    const uint32_t mid = f32_to_bf16_bits(r1);
-    const float r2 = r1 - bf16_bits_to_f32(mid);
-    const uint32_t lo = f32_to_bf16_bits(r2);
-    planes[i] = (uint16_t)hi;
-    planes[n + i] = (uint16_t)mid;
-    planes[2 * n + i] = (uint16_t)lo;
-}
+typedef __attribute__((ext_vector_type(2))) float rt_f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 rt_bf16x2;
 
-// 8 fp8 e4m3 payload bytes -> 8 bf16 (exact).
+// 8 fp8 e4m3 payload bytes -> 8 bf16.  An e4m3 value has 4 significant bits, so its binary32 form
+// has a zero low half and keeping the high half is exact: no rounding step is needed.
+__device__ inline uint32_t fp8x2_to_bf16x2(uint32_t word, bool high_pair)
+{
+    const rt_f32x2 f = high_pair ? __builtin_amdgcn_cvt_pk_f32_fp8(word, true) : __builtin_amdgcn_cvt_pk_f32_fp8(word, false);
+    return (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xffff0000u);
+}
 __device__ inline uint4 fp8x8_to_bf16x8(uint2 raw)
 {
     uint4 o;
-    o.x = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.x, 0), __builtin_amdgcn_cvt_f32_fp8(raw.x, 1));
-    o.y = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.x, 2), __builtin_amdgcn_cvt_f32_fp8(raw.x, 3));
-    o.z = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.y, 0), __builtin_amdgcn_cvt_f32_fp8(raw.y, 1));
-    o.w = pack_bf16x2(__builtin_amdgcn_cvt_f32_fp8(raw.y, 2), __builtin_amdgcn_cvt_f32_fp8(raw.y, 3));
+    o.x = fp8x2_to_bf16x2(raw.x, false);
+    o.y = fp8x2_to_bf16x2(raw.x, true);
+    o.z = fp8x2_to_bf16x2(raw.y, false);
+    o.w = fp8x2_to_bf16x2(raw.y, true);
     return o;
+}
+
+// Two fp32 router weights -> their three bf16 planes (hi, mid, lo: each the bf16 rounding, to nearest
+// even, of what the previous ones leave; the remainders are exact in fp32).
+__device__ inline void split_pair(float a, float b, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+{
+    const rt_bf16x2 h = __builtin_convertvector(rt_f32x2{a, b}, rt_bf16x2);
+    hi = __builtin_bit_cast(uint32_t, h);
+    const float ra = a - __uint_as_float(hi << 16), rb = b - __uint_as_float(hi & 0xffff0000u);
+    const rt_bf16x2 m = __builtin_convertvector(rt_f32x2{ra, rb}, rt_bf16x2);
+    mid = __builtin_bit_cast(uint32_t, m);
+    const float sa = ra - __uint_as_float(mid << 16), sb = rb - __uint_as_float(mid & 0xffff0000u);
+    const rt_bf16x2 l = __builtin_convertvector(rt_f32x2{sa, sb}, rt_bf16x2);
+    lo = __builtin_bit_cast(uint32_t, l);
 }
 
 template <bool FP8, int TB>
 __global__ __launch_bounds__(RM_THREADS) void router_logits_mfma_kernel(const void *__restrict__ x,
                                                                         const float *__restrict__ x_scale,
-                                                                        const uint16_t *__restrict__ planes,
+                                                                        const float *__restrict__ router_w,
                                                                         float *__restrict__ zpart, int T, int H, int E,
-                                                                        int k_per_split)
+                                                                        int k_per_split, int splits)
 {
     constexpr int BT = TB * 16;                            // tokens per workgroup
     constexpr int X_BYTES = BT * RM_BK * 2;                // one stage of token rows (bf16)
-    constexpr int W_BYTES = 3 * RM_BE * RM_BK * 2;         // one stage of the three planes
-    constexpr int STAGE = X_BYTES + W_BYTES;
     constexpr int XV = BT * 4 / RM_THREADS;                // 16-byte pieces of x per thread and stage (2 or 1)
-    constexpr int WV = 3 * RM_BE * 4 / RM_THREADS;         // 16-byte pieces of the planes per thread and stage (6)
+    constexpr int AHEAD = FP8 ? 2 : 3;                     // K steps whose loads are in flight (register budget)
     static_assert(XV >= 1 && BT * 4 % RM_THREADS == 0, "token tile must give every thread whole pieces");
-    extern __shared__ __align__(16) unsigned char rsm[];
+    extern __shared__ __align__(16) unsigned char rsm[];   // two stages of token rows; at the end the output tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
-    const int t0 = blockIdx.x * BT, e0 = blockIdx.y * RM_BE;
-    const int kbeg = blockIdx.z * k_per_split;
+    // Consecutive workgroups go to consecutive XCDs (eight, each with its own L2): the slice of H is
+    // the fastest index, so an XCD works on splits/8 (or one) slices of the router weights and keeps
+    // them in its L2 while the token tiles stream past.
+    const int zs = blockIdx.x % splits, xt = blockIdx.x / splits;
+    const int t0 = xt * BT, e0 = blockIdx.y * RM_BE;
+    const int kbeg = zs * k_per_split;
     const int kend = min(H, kbeg + k_per_split);
     const int nsteps = (kend - kbeg) / RM_BK;              // H and the split size are multiples of 32
-    const size_t plane = (size_t)E * H;
 
-    // loader coordinates: piece v of this thread is row (tid + v*512) / 4, 16-byte chunk (tid + v*512) % 4
-    uint4 xr[XV], wr[WV];
-    auto load_stage = [&](int step) {
+    // Token rows go through LDS (every wavefront needs all of them): piece v of this thread is row
+    // (tid + v*512) / 4, 16-byte chunk (tid + v*512) % 4.  The weights of a wavefront's 32 experts
+    // are needed by that wavefront alone, so they are loaded straight into the MFMA layout: lane
+    // (l16, lq) holds 8 consecutive k of expert l16 of each block.  Both are requested AHEAD steps
+    // before use (register sets in rotation).
+    auto load_x = [&](int step, uint4 (&xr)[XV]) __attribute__((always_inline)) {
         const int k0 = kbeg + step * RM_BK;
 #pragma unroll
         for (int v = 0; v < XV; ++v) {
             const int idx = tid + v * RM_THREADS, row = idx >> 2, ch = idx & 3;
-            const int t = t0 + row;
-            if (t < T) {
-                if constexpr (FP8) {
-                    const uint2 raw = *reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(x) + (size_t)t * H + k0 + ch * 8);
-                    xr[v] = fp8x8_to_bf16x8(raw);
-                } else {
-                    xr[v] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(x) + (size_t)t * H + k0 + ch * 8);
-                }
+            const int t = min(t0 + row, T - 1);            // rows past the end repeat the last token; never stored
+            if constexpr (FP8) {
+                const uint2 raw = *reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(x) + (size_t)t * H + k0 + ch * 8);
+                xr[v] = fp8x8_to_bf16x8(raw);
             } else {
-                xr[v] = uint4{0u, 0u, 0u, 0u};
+                xr[v] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(x) + (size_t)t * H + k0 + ch * 8);
             }
         }
-#pragma unroll
-        for (int v = 0; v < WV; ++v) {
-            const int idx = tid + v * RM_THREADS, pl = idx / (RM_BE * 4), row = (idx >> 2) % RM_BE, ch = idx & 3;
-            const int e = e0 + row;
-            wr[v] = e < E ? *reinterpret_cast<const uint4 *>(planes + pl * plane + (size_t)e * H + k0 + ch * 8)
-                          : uint4{0u, 0u, 0u, 0u};
-        }
     };
-    auto store_stage = [&](int buf) {
-        unsigned char *xs = rsm + buf * STAGE, *ws = xs + X_BYTES;
+    auto store_x = [&](int buf, const uint4 (&xr)[XV]) __attribute__((always_inline)) {
+        unsigned char *xs = rsm + buf * X_BYTES;
 #pragma unroll
         for (int v = 0; v < XV; ++v) *reinterpret_cast<uint4 *>(xs + (tid + v * RM_THREADS) * 16) = xr[v];
+    };
+    auto load_w = [&](int step, float4 (&wf)[2][2]) __attribute__((always_inline)) {
+        const int k = kbeg + step * RM_BK + lq * 8;
 #pragma unroll
-        for (int v = 0; v < WV; ++v) *reinterpret_cast<uint4 *>(ws + (tid + v * RM_THREADS) * 16) = wr[v];
+        for (int b = 0; b < 2; ++b) {
+            const int e = min(e0 + (wave * 2 + b) * 16 + l16, E - 1);   // experts past the end: never stored
+            const float4 *src = reinterpret_cast<const float4 *>(router_w + (size_t)e * H + k);
+            wf[b][0] = src[0];
+            wf[b][1] = src[1];
+        }
     };
 
     rt_f32x4 acc[2][TB];
@@ -259,19 +270,16 @@ __global__ __launch_bounds__(RM_THREADS) void router_logits_mfma_kernel(const vo
             if constexpr (FP8) blk[b][m] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
-    for (int s = 0; s < nsteps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < nsteps) load_stage(s + 1);             // in registers while this step computes
-        const unsigned char *xs = rsm + buf * STAGE, *ws = xs + X_BYTES;
-        rt_bf16x8 wf[2][3];
+    auto compute_step = [&](int s, const float4 (&wraw)[2][2]) __attribute__((always_inline)) {
+        const unsigned char *xs = rsm + (s & 1) * X_BYTES;
+        uint4 wr[2][3];                                    // [expert block][plane]: hi, mid, lo
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int pl = 0; pl < 3; ++pl)
-                wf[b][pl] = *reinterpret_cast<const rt_bf16x8 *>(ws + ((pl * RM_BE + (wave * 2 + b) * 16 + l16) * 4 + lq) * 16);
+        for (int b = 0; b < 2; ++b) {
+            split_pair(wraw[b][0].x, wraw[b][0].y, wr[b][0].x, wr[b][1].x, wr[b][2].x);
+            split_pair(wraw[b][0].z, wraw[b][0].w, wr[b][0].y, wr[b][1].y, wr[b][2].y);
+            split_pair(wraw[b][1].x, wraw[b][1].y, wr[b][0].z, wr[b][1].z, wr[b][2].z);
+            split_pair(wraw[b][1].z, wraw[b][1].w, wr[b][0].w, wr[b][1].w, wr[b][2].w);
+        }
 #pragma unroll
         for (int m = 0; m < TB; ++m) {
             const rt_bf16x8 tf = *reinterpret_cast<const rt_bf16x8 *>(xs + ((m * 16 + l16) * 4 + lq) * 16);
@@ -279,9 +287,9 @@ __global__ __launch_bounds__(RM_THREADS) void router_logits_mfma_kernel(const vo
             for (int b = 0; b < 2; ++b) {
                 rt_f32x4 &dst = FP8 ? blk[b][m] : acc[b][m];
                 // smallest plane first: the small contributions meet before the large one is added
-                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[b][2], tf, dst, 0, 0, 0);
-                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[b][1], tf, dst, 0, 0, 0);
-                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[b][0], tf, dst, 0, 0, 0);
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(rt_bf16x8, wr[b][2]), tf, dst, 0, 0, 0);
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(rt_bf16x8, wr[b][1]), tf, dst, 0, 0, 0);
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(rt_bf16x8, wr[b][0]), tf, dst, 0, 0, 0);
             }
         }
         if constexpr (FP8) {
@@ -300,22 +308,76 @@ __global__ __launch_bounds__(RM_THREADS) void router_logits_mfma_kernel(const vo
                 }
             }
         }
-        if (s + 1 < nsteps) store_stage(buf ^ 1);          // that buffer was last read in step s-1
-        __syncthreads();
-    }
+    };
 
-    // lane (l16, lq) holds, per expert block, experts 4*lq..4*lq+3 of token l16 of each token block
-    float *dst = zpart + (size_t)blockIdx.z * T * E;
+    // Step j uses register set j % AHEAD for its token rows (stored to LDS buffer j & 1 at the end
+    // of step j-1) and for its router weights; both sets are refilled for step j + AHEAD as soon as
+    // step j has used them.
+    uint4 xr0[XV], xr1[XV], xr2[XV];
+    float4 w0[2][2], w1[2][2], w2[2][2];
+    const int last = max(nsteps - 1, 0);                   // loads past the last step repeat it: no branches
+    load_x(0, xr0);
+    load_w(0, w0);
+    load_x(min(1, last), xr1);
+    load_w(min(1, last), w1);
+    if constexpr (AHEAD == 3) {
+        load_x(min(2, last), xr2);
+        load_w(min(2, last), w2);
+    }
+    store_x(0, xr0);
+    __syncthreads();
+#define RM_STEP(s_, W_, XCUR_, XNEXT_)                                                        \
+    {                                                                                         \
+        const int sj = (s_);                                                                  \
+        load_x(min(sj + AHEAD, last), XCUR_);        /* XCUR_ held step sj, already in LDS */  \
+        compute_step(sj, W_);                                                                 \
+        load_w(min(sj + AHEAD, last), W_);                                                    \
+        store_x((sj + 1) & 1, XNEXT_);               /* that buffer was last read in step sj-1 */ \
+        __syncthreads();                                                                      \
+    }
+    int s = 0;
+    if constexpr (AHEAD == 3) {
+        for (; s + 3 <= nsteps; s += 3) {
+            RM_STEP(s, w0, xr0, xr1)
+            RM_STEP(s + 1, w1, xr1, xr2)
+            RM_STEP(s + 2, w2, xr2, xr0)
+        }
+        if (s < nsteps) RM_STEP(s, w0, xr0, xr1)
+        if (s + 1 < nsteps) RM_STEP(s + 1, w1, xr1, xr2)
+    } else {
+        for (; s + 2 <= nsteps; s += 2) {
+            RM_STEP(s, w0, xr0, xr1)
+            RM_STEP(s + 1, w1, xr1, xr0)
+        }
+        if (s < nsteps) RM_STEP(s, w0, xr0, xr1)
+    }
+#undef RM_STEP
+
+    // Epilogue through LDS, so that the partial logits leave as whole rows: lane (l16, lq) holds, per
+    // expert block, experts 4*lq..4*lq+3 of token l16 of each token block; a row of the staged tile
+    // is one token's 256 logits (+16 bytes, which spreads the 16 tokens of a write over all banks).
+    // The last K step ended with a barrier, so the token stages are free to be overwritten.
+    constexpr int OUT_PITCH = RM_BE * 4 + 16;
 #pragma unroll
-    for (int m = 0; m < TB; ++m) {
-        const int t = t0 + m * 16 + l16;
-        if (t >= T) continue;
+    for (int m = 0; m < TB; ++m)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int e = e0 + (wave * 2 + b) * 16 + lq * 4;
+        for (int b = 0; b < 2; ++b)
+            *reinterpret_cast<rt_f32x4 *>(rsm + (m * 16 + l16) * OUT_PITCH + ((wave * 2 + b) * 16 + lq * 4) * 4) = acc[b][m];
+    __syncthreads();
+    float *dst = zpart + (size_t)zs * T * E;
+    const int e = e0 + lane * 4;
+    const bool vec = (E & 3) == 0 && e + 3 < E;
+    for (int r = wave; r < BT; r += RM_THREADS / 64) {
+        const int t = t0 + r;
+        if (t >= T) break;
+        const rt_f32x4 v = *reinterpret_cast<const rt_f32x4 *>(rsm + r * OUT_PITCH + lane * 16);
+        float *row = dst + (size_t)t * E + e;
+        if (vec) {
+            *reinterpret_cast<rt_f32x4 *>(row) = v;
+        } else {
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (e + v < E) dst[(size_t)t * E + e + v] = acc[b][m][v];
+            for (int j = 0; j < 4; ++j)
+                if (e + j < E) row[j] = v[j];
         }
     }
 }
@@ -479,15 +541,31 @@ __global__ __launch_bounds__(256) void router_topk_kernel(const float *__restric
     // together so that their latencies overlap
 #pragma unroll
     for (int i = 0; i < EPL; ++i) z[i] = 0.f;
+    const bool whole = E % EPL == 0;                       // a lane's experts are all inside or all outside: one wide load
     for (int sp0 = 0; sp0 < p.splits; sp0 += 8) {
         float part[8][EPL];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < 8; ++u) {
+            const float *src = zpart + ((size_t)(sp0 + u) * p.T + t) * E + lane * EPL;
+            const bool live = sp0 + u < p.splits;
+            if (whole) {
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) {
-                const int e = lane * EPL + i;
-                part[u][i] = (e < E && sp0 + u < p.splits) ? zpart[((size_t)(sp0 + u) * p.T + t) * E + e] : 0.f;
+                for (int i = 0; i < EPL; ++i) part[u][i] = 0.f;
+                if (live && lane * EPL < E) {
+                    typedef float wide_t __attribute__((ext_vector_type(EPL < 4 ? EPL : 4)));
+                    constexpr int WN = EPL < 4 ? EPL : 4;
+#pragma unroll
+                    for (int q = 0; q < EPL / WN; ++q) {
+                        const wide_t v = reinterpret_cast<const wide_t *>(src)[q];
+#pragma unroll
+                        for (int i = 0; i < WN; ++i) part[u][q * WN + i] = v[i];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) part[u][i] = (live && lane * EPL + i < E) ? src[i] : 0.f;
             }
+        }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
 #pragma unroll
@@ -594,7 +672,7 @@ MfmaGrid mfma_grid(const moe_config &c)
     MfmaGrid g{};
     g.use = c.T >= RM_MIN_TOKENS && c.E > RT_FEW && c.H % RM_BK == 0;
     if (!g.use) return g;
-    g.tb = 8;                                              // 128 tokens per workgroup (256 measured 9 % slower: twice the partial logits)         // fp8 keeps a second accumulator set per scale block
+    g.tb = 8;                                              // 128 tokens per workgroup (256 measured 9 % slower: twice the partial logits)
     g.tiles_t = ceil_div(c.T, g.tb * 16);
     g.tiles_e = ceil_div(c.E, RM_BE);
     const int chunks = c.H / RM_BK;
@@ -614,7 +692,7 @@ size_t route_workspace_bytes(const moe_config &c)
     if (c.E <= RT_FEW) return 256;
     const MfmaGrid m = mfma_grid(c);
     if (m.use)
-        return align_up((size_t)m.splits * c.T * c.E * sizeof(float), 256) + align_up((size_t)3 * c.E * c.H * 2, 256);
+        return align_up((size_t)m.splits * c.T * c.E * sizeof(float), 256);
     const RouteGrid g = route_grid(c);
     return align_up((size_t)g.splits * c.T * c.E * sizeof(float), 256);
 }
@@ -648,17 +726,11 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
     float *zpart = static_cast<float *>(ws);
     const MfmaGrid m = mfma_grid(c);
     if (m.use) {
-        uint16_t *planes = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(ws) +
-                                                        align_up((size_t)m.splits * c.T * c.E * sizeof(float), 256));
-        const size_t n = (size_t)c.E * c.H;
-        hipLaunchKernelGGL(router_split_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, router_w,
-                           planes, n);
-        int rc = check_launch();
-        if (rc != MOE_OK) return rc;
-        const dim3 grid(m.tiles_t, m.tiles_e, m.splits);
+        int rc;
+        const dim3 grid(m.tiles_t * m.splits, m.tiles_e, 1);
         if (c.dtype == MOE_DTYPE_FP8_E4M3) {
             auto kern = router_logits_mfma_kernel<true, 8>;
-            constexpr int lds = 2 * (8 * 16 * RM_BK * 2 + 3 * RM_BE * RM_BK * 2);
+            constexpr int lds = 8 * 16 * (RM_BE * 4 + 16);   // the staged output tile (the two token stages fit inside)
             static bool attr_done = false;
             if (!attr_done) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -666,11 +738,11 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
                 if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
                 attr_done = true;
             }
-            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, planes, zpart, c.T, c.H, c.E,
-                               m.k_per_split);
+            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, router_w, zpart, c.T, c.H, c.E,
+                               m.k_per_split, m.splits);
         } else {
             auto kern = router_logits_mfma_kernel<false, 8>;
-            constexpr int lds = 2 * (8 * 16 * RM_BK * 2 + 3 * RM_BE * RM_BK * 2);
+            constexpr int lds = 8 * 16 * (RM_BE * 4 + 16);   // the staged output tile (the two token stages fit inside)
             static bool attr_done = false;
             if (!attr_done) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -678,8 +750,8 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
                 if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
                 attr_done = true;
             }
-            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, planes, zpart, c.T, c.H, c.E,
-                               m.k_per_split);
+            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, router_w, zpart, c.T, c.H, c.E,
+                               m.k_per_split, m.splits);
         }
         rc = check_launch();
         if (rc != MOE_OK) return rc;
