@@ -55,6 +55,11 @@ CASES = {
     "low_tiles_ragged": syn.Workload("low_tiles_ragged", T=256, H=1600, I=64, E=256, top_k=8),   # 3 slabs of 512 columns + 64
     "low_tiles_fp8": syn.Workload("low_tiles_fp8", T=250, H=2048, I=128, E=256, top_k=8, n_group=8, topk_group=4,
                                   fp8=True, **GROUPED),
+    # matrix-core router with several K steps per workgroup (5: the rotation of its three register
+    # sets ends mid-cycle), two expert tiles with a ragged second one, an expert count that is no
+    # multiple of 4 (element-wise stores and loads of the partial logits), a ragged token tile
+    "router_deep": syn.Workload("router_deep", T=1300, H=1920, I=64, E=330, top_k=4),
+    "router_deep_fp8": syn.Workload("router_deep_fp8", T=1300, H=1920, I=128, E=132, top_k=4, fp8=True),
     # the limits of the interface: 512 experts (8 per lane in the router) and 64 experts per token
     "max_experts": syn.Workload("max_experts", T=40, H=128, I=64, E=512, top_k=64),
 }
