@@ -397,32 +397,66 @@ __device__ inline unsigned long long pack_key(float c, int e)
     return ((unsigned long long)orderable(c) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)e);
 }
 
-__device__ inline unsigned long long shfl_xor_u64(unsigned long long v, int mask)
+// Partner exchange of an all-reduce butterfly over the 64 lanes, step by step (STEP = 0..5 joins
+// groups of 2^STEP lanes into groups of twice the size).  Inside a row of 16 lanes the value
+// comes through DPP, which costs no more than the ALU operation it feeds: swaps inside a quad for
+// steps 0 and 1, then the mirror images of 8 and of 16 lanes (after the earlier steps all lanes of
+// a group hold the same value, so any lane of the other group serves).  Step 4 crosses rows with
+// a swizzle, step 5 crosses the two halves of the wavefront with a lane permute; only those two
+// go through the LDS crossbar.
+template <int STEP>
+__device__ __forceinline__ uint32_t butterfly_partner(uint32_t v)
 {
-    const uint32_t lo = __shfl_xor((int)(uint32_t)v, mask, kWave);
-    const uint32_t hi = __shfl_xor((int)(uint32_t)(v >> 32), mask, kWave);
-    return ((unsigned long long)hi << 32) | lo;
+    static_assert(STEP >= 0 && STEP <= 5, "64 lanes");
+    if constexpr (STEP == 0) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
+    else if constexpr (STEP == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+    else if constexpr (STEP == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);  // row_half_mirror
+    else if constexpr (STEP == 3) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, false);  // row_mirror
+    else if constexpr (STEP == 4) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F);                     // lane ^ 16
+    else return (uint32_t)__shfl_xor((int)v, 32, kWave);
 }
 
-// max over aligned segments of `width` lanes (width = power of two <= 64)
+template <int STEP>
+__device__ __forceinline__ unsigned long long butterfly_max_u64(unsigned long long v)
+{
+    const uint32_t lo = butterfly_partner<STEP>((uint32_t)v);
+    const uint32_t hi = butterfly_partner<STEP>((uint32_t)(v >> 32));
+    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    return o > v ? o : v;
+}
+
+// max over aligned segments of `width` lanes (width = power of two <= 64; the same on every lane)
 __device__ inline unsigned long long seg_max_u64(unsigned long long v, int width)
 {
-    for (int m = 1; m < width; m <<= 1) {
-        const unsigned long long o = shfl_xor_u64(v, m);
-        v = o > v ? o : v;
-    }
+    if (width > 1) v = butterfly_max_u64<0>(v);
+    if (width > 2) v = butterfly_max_u64<1>(v);
+    if (width > 4) v = butterfly_max_u64<2>(v);
+    if (width > 8) v = butterfly_max_u64<3>(v);
+    if (width > 16) v = butterfly_max_u64<4>(v);
+    if (width > 32) v = butterfly_max_u64<5>(v);
     return v;
 }
 
 __device__ inline float wave_max_f32(float v)
 {
-    for (int m = 1; m < kWave; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+    v = fmaxf(v, __uint_as_float(butterfly_partner<0>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(butterfly_partner<1>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(butterfly_partner<2>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(butterfly_partner<3>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(butterfly_partner<4>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(butterfly_partner<5>(__float_as_uint(v))));
     return v;
 }
 
+// Every lane adds the same two operands at every step, so all lanes end with the same value.
 __device__ inline float wave_sum_f32(float v)
 {
-    for (int m = 1; m < kWave; m <<= 1) v += __shfl_xor(v, m, kWave);   // butterfly: same value on every lane
+    v += __uint_as_float(butterfly_partner<0>(__float_as_uint(v)));
+    v += __uint_as_float(butterfly_partner<1>(__float_as_uint(v)));
+    v += __uint_as_float(butterfly_partner<2>(__float_as_uint(v)));
+    v += __uint_as_float(butterfly_partner<3>(__float_as_uint(v)));
+    v += __uint_as_float(butterfly_partner<4>(__float_as_uint(v)));
+    v += __uint_as_float(butterfly_partner<5>(__float_as_uint(v)));
     return v;
 }
 
