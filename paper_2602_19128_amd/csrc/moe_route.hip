@@ -560,7 +560,10 @@ __device__ __forceinline__ void route_token(const float (&z)[EPL], int lane, int
 }
 
 // One wavefront per token: adds the partial logits of the H splits, then routes the token.
-template <int EPL>
+// NB = splits whose partial logits are requested together (8, or 32 when H was cut into more than
+// 8 slices - few tokens, so registers are not what limits the kernel, the latency of one round of
+// loads after another is: 64 decode tokens 17 -> 9 us).
+template <int EPL, int NB>
 __global__ __launch_bounds__(256) void router_topk_kernel(const float *__restrict__ zpart,
                                                           const float *__restrict__ bias,
                                                           int32_t *__restrict__ ids, float *__restrict__ w,
@@ -571,37 +574,46 @@ __global__ __launch_bounds__(256) void router_topk_kernel(const float *__restric
     if (t >= p.T) return;                                  // whole wave leaves together
     const int E = p.E;
     float z[EPL];
-    // partial logits of the H splits, added in split order; the loads of eight splits are issued
+    // partial logits of the H splits, added in split order; the loads of NB splits are issued
     // together so that their latencies overlap
 #pragma unroll
     for (int i = 0; i < EPL; ++i) z[i] = 0.f;
+    // Every load is unconditional (split and expert indices are clamped, what lies outside is
+    // zeroed afterwards): a load under a branch would be waited for before the next one is issued.
     const bool whole = E % EPL == 0;                       // a lane's experts are all inside or all outside: one wide load
-    for (int sp0 = 0; sp0 < p.splits; sp0 += 8) {
-        float part[8][EPL];
+    for (int sp0 = 0; sp0 < p.splits; sp0 += NB) {
+        float part[NB][EPL];
+        if (whole) {
+            typedef float wide_t __attribute__((ext_vector_type(EPL < 4 ? EPL : 4)));
+            constexpr int WN = EPL < 4 ? EPL : 4;
+            const int e_lane = min(lane * EPL, E - EPL);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float *src = zpart + ((size_t)(sp0 + u) * p.T + t) * E + lane * EPL;
-            const bool live = sp0 + u < p.splits;
-            if (whole) {
+            for (int u = 0; u < NB; ++u) {
+                const int sp = min(sp0 + u, p.splits - 1);
+                const wide_t *src = reinterpret_cast<const wide_t *>(zpart + ((size_t)sp * p.T + t) * E + e_lane);
 #pragma unroll
-                for (int i = 0; i < EPL; ++i) part[u][i] = 0.f;
-                if (live && lane * EPL < E) {
-                    typedef float wide_t __attribute__((ext_vector_type(EPL < 4 ? EPL : 4)));
-                    constexpr int WN = EPL < 4 ? EPL : 4;
+                for (int q = 0; q < EPL / WN; ++q) {
+                    const wide_t v = src[q];
 #pragma unroll
-                    for (int q = 0; q < EPL / WN; ++q) {
-                        const wide_t v = reinterpret_cast<const wide_t *>(src)[q];
-#pragma unroll
-                        for (int i = 0; i < WN; ++i) part[u][q * WN + i] = v[i];
-                    }
+                    for (int i = 0; i < WN; ++i) part[u][q * WN + i] = v[i];
                 }
-            } else {
+            }
+        } else {
 #pragma unroll
-                for (int i = 0; i < EPL; ++i) part[u][i] = (live && lane * EPL + i < E) ? src[i] : 0.f;
+            for (int u = 0; u < NB; ++u) {
+                const int sp = min(sp0 + u, p.splits - 1);
+                const float *src = zpart + ((size_t)sp * p.T + t) * E;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) part[u][i] = src[min(lane * EPL + i, E - 1)];
             }
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+            for (int i = 0; i < EPL; ++i)
+                if (sp0 + u >= p.splits || lane * EPL + i >= E) part[u][i] = 0.f;
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
 #pragma unroll
             for (int i = 0; i < EPL; ++i) z[i] += part[u][i];
     }
@@ -806,12 +818,17 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
 
     const dim3 tgrid(ceil_div(c.T, 4));
     const int epl = c.E <= 64 ? 1 : c.E <= 128 ? 2 : c.E <= 256 ? 4 : 8;
+    const bool many = p.splits > 8;
+#define MOE_LAUNCH_TOPK(EPL_)                                                                                       \
+    if (many) hipLaunchKernelGGL((router_topk_kernel<EPL_, RT_MAX_SPLIT>), tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); \
+    else hipLaunchKernelGGL((router_topk_kernel<EPL_, 8>), tgrid, dim3(256), 0, s, zpart, bias, ids, w, p);
     switch (epl) {
-    case 1: hipLaunchKernelGGL(router_topk_kernel<1>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
-    case 2: hipLaunchKernelGGL(router_topk_kernel<2>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
-    case 4: hipLaunchKernelGGL(router_topk_kernel<4>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
-    default: hipLaunchKernelGGL(router_topk_kernel<8>, tgrid, dim3(256), 0, s, zpart, bias, ids, w, p); break;
+    case 1: MOE_LAUNCH_TOPK(1) break;
+    case 2: MOE_LAUNCH_TOPK(2) break;
+    case 4: MOE_LAUNCH_TOPK(4) break;
+    default: MOE_LAUNCH_TOPK(8) break;
     }
+#undef MOE_LAUNCH_TOPK
     return check_launch();
 }
 
