@@ -86,7 +86,8 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
 #pragma unroll
         for (int j = 0; j < PM_BATCH; ++j) {
             const int p = base + j * PM_THREADS + tid;
-            ev[j] = (p < P) ? ids[p] - e_first : -1;
+            const int e = ids[min(p, P - 1)] - e_first;      // unconditional: a load under a branch is waited for at once
+            ev[j] = (p < P) ? e : -1;
         }
 #pragma unroll
         for (int j = 0; j < PM_BATCH; ++j) {
@@ -191,7 +192,8 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
 #pragma unroll
         for (int j = 0; j < PM_BATCH; ++j) {
             const int p = base0 + j * kWave + lane;
-            ev[j] = (p < p_end) ? ids[p] - e_first : -1;
+            const int e = ids[min(p, P - 1)] - e_first;
+            ev[j] = (p < p_end) ? e : -1;
         }
 #pragma unroll
         for (int j = 0; j < PM_BATCH; ++j) {
