@@ -5,6 +5,8 @@
 //   router_logits_kernel  z = x . router_w^T in fp32, LDS-tiled, split along H so that a
 //                         handful of decode tokens still fills the chip; partial sums go
 //                         to scratch and are added in a fixed order (deterministic).
+//   router_logits_mfma_kernel  the same partial sums on the matrix cores (512 tokens and more):
+//                         three bf16 MFMAs per block carry the fp32 weights exactly.
 //   router_topk_kernel    one 64-lane wavefront per token: scoring rule, optional
 //                         group limiting, then k rounds of a cross-lane arg-max.
 #include "moe_internal.hpp"
