@@ -3,12 +3,16 @@
 // Each thread owns 8 consecutive hidden elements of one token and walks the token's
 // k expert rows in slot order (their loads requested eight at a time), so the fp32 sum
 // has one fixed order and needs no atomics; the result is rounded once to bf16
-// (nearest-even).
+// (nearest-even).  NT: the expert rows are read with non-temporal loads - right when [P,H] is far
+// larger than the L2s and was streamed out by the down projection (4096 DeepSeek tokens: 103 ->
+// 80 us); wrong when only a share of the experts is local and the few rows that exist are still
+// cached (measured 24 -> 29 us on a 32-of-256 share), so the launch picks.
 #include "moe_internal.hpp"
 
 namespace moe {
 namespace {
 
+template <bool NT>
 __global__ __launch_bounds__(256) void combine_kernel(const uint16_t *__restrict__ y,
                                                       const float *__restrict__ w,
                                                       const int32_t *__restrict__ inv,
@@ -35,7 +39,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t *__restrict
         }
 #pragma unroll
         for (int u = 0; u < CB; ++u)
-            raw[u] = row[u] >= 0 ? *reinterpret_cast<const uint4 *>(y + (size_t)row[u] * H + h) : uint4{0u, 0u, 0u, 0u};
+        {
+            typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (row[u] >= 0) {
+                const u32x4_t *src = reinterpret_cast<const u32x4_t *>(y + (size_t)row[u] * H + h);
+                v = NT ? __builtin_nontemporal_load(src) : *src;
+            }
+            raw[u] = uint4{v[0], v[1], v[2], v[3]};
+        }
 #pragma unroll
         for (int u = 0; u < CB; ++u) {
             if (row[u] < 0) continue;                      // a pair without a row (its expert is held elsewhere)
@@ -62,8 +74,13 @@ int launch_combine(const moe_config &c, const void *y, const float *w, const int
 {
     const long long work = (long long)c.T * (c.H / 8);
     const unsigned blocks = (unsigned)((work + 255) / 256);
-    hipLaunchKernelGGL(combine_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const uint16_t *>(y), w, inv,
-                       static_cast<uint16_t *>(out), c.T, c.H, c.top_k);
+    const bool streamed = local_experts(c) == c.E && (size_t)c.T * c.top_k * c.H * 2 > ((size_t)32 << 20);
+    if (streamed)
+        hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(256), 0, s, static_cast<const uint16_t *>(y), w, inv,
+                           static_cast<uint16_t *>(out), c.T, c.H, c.top_k);
+    else
+        hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(256), 0, s, static_cast<const uint16_t *>(y), w, inv,
+                           static_cast<uint16_t *>(out), c.T, c.H, c.top_k);
     return check_launch();
 }
 

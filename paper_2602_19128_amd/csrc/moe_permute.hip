@@ -25,7 +25,7 @@ namespace {
 constexpr int PM_THREADS = 1024;
 constexpr int PM_WAVES = PM_THREADS / kWave;
 constexpr int PM_BATCH = 8;             // 64-pair batches whose ids are loaded together
-constexpr int PM_SLICE = 2048;          // pairs placed by one workgroup
+constexpr int PM_SLICE = 1024;          // pairs placed by one workgroup (one 64-pair batch per wavefront)
 constexpr int PM_MAX_WGS = 64;
 
 // Inclusive scan of n <= kMaxExperts ints held in LDS (Hillis-Steele, all threads sync).
