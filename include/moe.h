@@ -20,7 +20,12 @@
  *   - Same inputs give bit-identical outputs (no floating-point atomics anywhere).
  *   - Return value: MOE_OK or a negative error code; nothing is enqueued when an
  *     argument check fails.
- *   - Shapes: H and I multiples of 64 (128 for fp8), E <= 512, top_k <= min(E,64).
+ *   - Threads: any number of host threads may call in at the same time (the only
+ *     shared host state is a once-per-device kernel set-up that tolerates it); the
+ *     error of moe_last_hip_error() is per thread.  Calls that share a workspace or
+ *     an output must not overlap on the device: put them on one stream.
+ *   - Shapes: H and I multiples of 64 (128 for fp8, and at most 16384 there),
+ *     E <= 512, top_k <= min(E,64).
  *     Group-limited routing needs E % n_group == 0, a power-of-two number of
  *     lanes per group (see moe_route) and top_k <= topk_group * E / n_group.
  *   - Notation: T tokens, H hidden size, I expert intermediate size, E experts,
@@ -43,6 +48,10 @@
 
 #include <stddef.h>
 #include <stdint.h>
+
+/* The library is built with hidden symbol visibility; the entry points below are its whole
+ * exported surface. */
+#define MOE_API __attribute__((visibility("default")))
 
 #ifdef __cplusplus
 extern "C" {
@@ -84,8 +93,8 @@ typedef struct moe_config {
 /* Row count of one tile of the grouped GEMMs for this problem (the height the
  * tile list produced by moe_permute is cut to), and the capacity, in tiles, the
  * caller must give the tile list. */
-int32_t moe_tile_rows(const moe_config *cfg);
-int32_t moe_max_tiles(const moe_config *cfg);
+MOE_API int32_t moe_tile_rows(const moe_config *cfg);
+MOE_API int32_t moe_max_tiles(const moe_config *cfg);
 
 /* One tile-list record: rows [row0, row0+rows) of the expert-sorted order all
  * belong to `expert`; `first` is the index of that expert's first record and
@@ -109,8 +118,8 @@ typedef struct moe_tile {
 enum { MOE_WORK_RANGES = 8, MOE_SCHED_INTS = 16 };
 
 /* Bytes of device scratch moe_route / moe_forward need for this problem. */
-size_t moe_route_workspace_size(const moe_config *cfg);
-size_t moe_workspace_size(const moe_config *cfg);
+MOE_API size_t moe_route_workspace_size(const moe_config *cfg);
+MOE_API size_t moe_workspace_size(const moe_config *cfg);
 
 /*
  * Routing (paper Sec. 4.5 "Routing": score all experts per token, keep the top-k).
@@ -124,7 +133,7 @@ size_t moe_workspace_size(const moe_config *cfg);
  *   workspace device scratch of at least moe_route_workspace_size(cfg) bytes
  * Non-finite inputs give unspecified but in-range ids.
  */
-int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+MOE_API int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
               const float *bias, int32_t *ids_out, float *w_out,
               void *workspace, size_t workspace_bytes, void *stream);
 
@@ -137,7 +146,7 @@ int moe_route(const moe_config *cfg, const void *x, const float *x_scale, const 
  *   x [T,H] bf16 -> xq_out [T,H] fp8 e4m3 (OCP e4m3fn), x_scale_out [T,H/128] fp32; H % 128 == 0.
  * cfg->dtype and cfg->quantize_x are not consulted; T and H are.
  */
-int moe_quantize_act(const moe_config *cfg, const void *x, void *xq_out, float *x_scale_out, void *stream);
+MOE_API int moe_quantize_act(const moe_config *cfg, const void *x, void *xq_out, float *x_scale_out, void *stream);
 
 /*
  * Sort-scatter (paper Sec. 4.5: reorder tokens by expert into contiguous memory).
@@ -154,7 +163,7 @@ int moe_quantize_act(const moe_config *cfg, const void *x, void *xq_out, float *
  *                indexes w1 / w2)
  *   sched_out    [MOE_SCHED_INTS] int32: records written and the work ranges (see moe_tile)
  */
-int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
+MOE_API int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
                 int32_t *sorted_pair_out, int32_t *inv_out, moe_tile *tiles_out,
                 int32_t *sched_out, void *stream);
 
@@ -168,7 +177,7 @@ int moe_permute(const moe_config *cfg, const int32_t *ids, int32_t *offsets_out,
  *   fp8 : w1_scale [EL,2I/128,H/128], x_scale [T,H/128]; act_out [P,I] fp8 e4m3 and
  *         act_scale_out [P,I/128] fp32 (act re-quantised per 1x128 block, scale = amax/448).
  */
-int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x_scale,
+MOE_API int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x_scale,
                             const void *w1, const float *w1_scale, const int32_t *sorted_pair,
                             const moe_tile *tiles, const int32_t *sched,
                             void *act_out, float *act_scale_out, void *stream);
@@ -178,7 +187,7 @@ int moe_grouped_gemm_swiglu(const moe_config *cfg, const void *x, const float *x
  *   y[r,h] = act[r,:] . w2[e,h,:],  w2 [EL,H,I], fp32 accumulation, y_out [P,H] bf16.
  *   fp8: act_scale [P,I/128], w2_scale [EL,H/128,I/128]; else NULL.
  */
-int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *act_scale,
+MOE_API int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *act_scale,
                           const void *w2, const float *w2_scale, const moe_tile *tiles,
                           const int32_t *sched, void *y_out, void *stream);
 
@@ -186,20 +195,25 @@ int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *a
  * Weighted combine: out[t,:] = sum_{j<k} w[t,j] * y[inv[t*k+j],:], summed in slot
  * order in fp32 (no atomics), rounded to bf16 (nearest-even).  Dropped pairs
  * (inv < 0) contribute nothing.
+ * The paper's description of the operator (Sec. 4.5) ends with the down projection and
+ * defines no combine; this step is what the definition of a top-k MoE layer adds to it:
+ * a token's output is the sum of its k experts' outputs, each times its routing weight.
  *   y [P,H] bf16, w [T,k] fp32, inv [P] int32, out [T,H] bf16.
  */
-int moe_combine(const moe_config *cfg, const void *y, const float *w, const int32_t *inv,
+MOE_API int moe_combine(const moe_config *cfg, const void *y, const float *w, const int32_t *inv,
                 void *out, void *stream);
 
 /*
- * The whole layer: the five steps above enqueued back to back on `stream`,
+ * The whole layer (paper Sec. 4.5: routing, sort-scatter, expert FFN; the paper names no
+ * entry point of its own, the argument list is the problem statement: hidden states,
+ * router weights, expert weights, optional block scales): the five steps above enqueued back to back on `stream`,
  * intermediates in `workspace` (>= moe_workspace_size(cfg) bytes, 256-byte aligned).
  * bias / *_scale may be NULL as described per step.  out [T,H] bf16.
  * With cfg->quantize_x, x is [T,H] bf16 and x_scale is ignored: moe_quantize_act runs first
  * (its outputs live in the workspace), the router reads the bf16 x, the gate/up GEMM the
  * quantised copy.
  */
-int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+MOE_API int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
                 const float *bias, const void *w1, const float *w1_scale, const void *w2,
                 const float *w2_scale, void *out, void *workspace, size_t workspace_bytes,
                 void *stream);
@@ -213,14 +227,14 @@ int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, cons
  * launch configuration are exactly those of moe_forward.
  */
 enum { MOE_FORWARD_EVENTS = 6 };
-int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+MOE_API int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
                        const float *bias, const void *w1, const float *w1_scale, const void *w2,
                        const float *w2_scale, void *out, void *workspace, size_t workspace_bytes,
                        void *stream, void *const *events);
 
 /* Text for an error code; the hipError_t of the last failed launch on this thread. */
-const char *moe_error_string(int code);
-int moe_last_hip_error(void);
+MOE_API const char *moe_error_string(int code);
+MOE_API int moe_last_hip_error(void);
 
 #ifdef __cplusplus
 }

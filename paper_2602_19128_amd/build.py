@@ -1,13 +1,19 @@
 """Builds the HIP library in-tree: paper_2602_19128_amd/libmoe_gfx950.so.
 
     python -m paper_2602_19128_amd.build
+
+Every csrc/*.hip file is one translation unit; they are compiled side by side and linked
+into one shared object that exports the C ABI of include/moe.h and nothing else.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import glob
 import os
+import shutil
 import subprocess
 import sys
+import tempfile
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
@@ -15,30 +21,47 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoe_gfx950.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    "-fvisibility=hidden",                                          # only MOE_API symbols leave the library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
     "-Wall", "-Wno-unused-function",
 ]
+# the host pass reports the device-only target feature as unknown; that line is noise
+_NOISE = "is not a recognized feature for this target"
 
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = True) -> str:
-    """Compile every HIP source for gfx950 and link the shared library (always rebuilds)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *sources()]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    # the host pass reports the device-only target feature as unknown; that line is noise
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    err = "\n".join(l for l in res.stderr.splitlines() if _NOISE not in l)
     if err.strip() and verbose:
         print(err, file=sys.stderr)
     if res.returncode != 0:
-        raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
+        raise RuntimeError(f"hipcc failed ({res.returncode}): {' '.join(cmd)}\n{err}")
+
+
+def build(verbose: bool = True, jobs: int = 0) -> str:
+    """Compile every HIP source for gfx950 and link the shared library (always rebuilds)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    srcs = sources()
+    jobs = jobs or min(len(srcs), max(1, min(16, os.cpu_count() or 1)))
+    tmp = tempfile.mkdtemp(prefix="moe_build_")
+    try:
+        objs = [os.path.join(tmp, os.path.basename(s)[:-4] + ".o") for s in srcs]
+        with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+            futs = [pool.submit(_run, [hipcc, *HIPCC_FLAGS, *inc, "-c", s, "-o", o], verbose)
+                    for s, o in zip(srcs, objs)]
+            for f in futs:
+                f.result()
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], verbose)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return LIB
 
 

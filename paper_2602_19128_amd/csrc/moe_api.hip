@@ -23,6 +23,9 @@ int validate(const moe_config *c)
     if (c->E > kMaxExperts || c->top_k > kMaxTopK) return MOE_ERR_UNSUPPORTED;
     if (c->H % 64 != 0 || c->I % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if (c->dtype == MOE_DTYPE_FP8_E4M3 && (c->H % kQBlock != 0 || c->I % kQBlock != 0)) return MOE_ERR_UNSUPPORTED;
+    // fp8 GEMMs keep a column slab's weight scales for the whole contraction in two registers per lane
+    if (c->dtype == MOE_DTYPE_FP8_E4M3 && (c->H > kMaxScaleBlocks * kQBlock || c->I > kMaxScaleBlocks * kQBlock))
+        return MOE_ERR_UNSUPPORTED;
     if ((long long)c->T * c->top_k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
     if (c->local_expert_offset < 0 || c->num_local_experts < 0) return MOE_ERR_INVALID;
     if (c->num_local_experts == 0 && c->local_expert_offset != 0) return MOE_ERR_INVALID;

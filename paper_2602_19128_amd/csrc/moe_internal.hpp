@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "moe.h"
 
 namespace moe {
@@ -12,6 +14,7 @@ constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kMaxExperts = 512;
 constexpr int kMaxTopK = 64;
 constexpr int kQBlock = 128;         // edge of an fp8 scale block
+constexpr int kMaxScaleBlocks = 128; // fp8: scale blocks along a contraction (H or I up to 16384)
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -45,6 +48,34 @@ inline int check_launch()
     return MOE_OK;
 }
 
+// One-time set-up per device (e.g. a kernel's dynamic-LDS limit), safe to reach from several host
+// threads: the set-up must be idempotent, since two threads may both run it before either has
+// marked it done; a failed set-up is tried again by the next call.
+constexpr int kMaxDevices = 64;
+struct DeviceOnce {
+    std::atomic<int> done[kMaxDevices];
+    DeviceOnce() { for (auto &d : done) d.store(0, std::memory_order_relaxed); }
+    template <class F> int run(F &&setup)
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return setup();
+        if (done[dev].load(std::memory_order_acquire)) return MOE_OK;
+        const int rc = setup();
+        if (rc == MOE_OK) done[dev].store(1, std::memory_order_release);
+        return rc;
+    }
+};
+
+// Raises a kernel's dynamic-LDS limit, once per device.
+inline int set_dynamic_lds(DeviceOnce &once, const void *kern, int bytes)
+{
+    return once.run([&]() {
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
+        return MOE_OK;
+    });
+}
+
 // ---- per-step launchers (arguments already validated by the C ABI layer) -----
 size_t route_workspace_bytes(const moe_config &c);
 int launch_route(const moe_config &c, const void *x, const float *x_scale, const float *router_w,
@@ -62,5 +93,31 @@ int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const vo
                      const moe_tile *tiles, const int32_t *sched, void *y, hipStream_t s);
 int launch_combine(const moe_config &c, const void *y, const float *w, const int32_t *inv, void *out,
                    hipStream_t s);
+
+// ---- grouped GEMMs: operand description shared by the host side and the kernel instantiations ----
+constexpr int GM_STEP_BYTES = 128;        // bytes of every row consumed per K step
+
+struct GemmArgs {
+    const unsigned char *A;       // gate/up: x [T,K]; down: act [P,K]
+    const float *a_scale;         // fp8: [T or P, K/128]
+    const unsigned char *W;       // [E, w_rows, K]
+    const float *w_scale;         // fp8: [E, w_rows/128, K/128]
+    const int32_t *sorted_pair;   // gate/up only
+    unsigned char *out;           // gate/up: act [P,n_out] (bf16 / fp8); down: y [P,n_out] bf16
+    float *out_scale;             // fp8 gate/up: act_scale [P, n_out/128]
+    int K, n_out, top_k;
+    int k_groups;                 // distinct K-loop starting points spread over the workgroups (1 = all start at 0)
+    int nt_out;                   // write the output with non-temporal stores (it is too large to stay in L2 anyway)
+};
+
+// kernel instantiations per operand type (moe_gemm_{gateup,down}_{bf16,fp8}.hip)
+int launch_gemm_gateup_bf16(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
+                            int max_tiles, int est_tiles, hipStream_t s);
+int launch_gemm_gateup_fp8(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
+                           int max_tiles, int est_tiles, hipStream_t s);
+int launch_gemm_down_bf16(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
+                          int max_tiles, int est_tiles, hipStream_t s);
+int launch_gemm_down_fp8(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
+                         int max_tiles, int est_tiles, hipStream_t s);
 
 }  // namespace moe

@@ -208,15 +208,21 @@ __global__ __launch_bounds__(PM_THREADS) void permute_kernel(const int32_t *__re
                 same &= ((e >> b) & 1) ? m : ~m;
             }
             const unsigned long long lower = (1ull << lane) - 1ull;
+            const int at = cursor[valid ? e : 0];          // every lane of an expert reads its cursor ...
+            __builtin_amdgcn_wave_barrier();               // ... before the first of them advances it
             if (valid) {
                 const int rank = __popcll(same & lower);
-                const int row = cursor[e] + rank;
+                const int row = at + rank;
                 sorted_pair[row] = p;
                 inv[p] = row;
-                if (rank == 0) cursor[e] = cursor[e] + __popcll(same);   // one lane per expert advances it
+                if (rank == 0) cursor[e] = at + __popcll(same);
             } else if (p < p_end) {
                 inv[p] = -1;
             }
+            // the next batch reads the cursors this one advanced: keep the wavefront's LDS accesses in order
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
 }

@@ -712,6 +712,9 @@ __global__ __launch_bounds__(256) void router_few_experts_kernel(const void *__r
 
 }  // namespace
 
+constexpr int RM_OUT_LDS = 8 * 16 * (RM_BE * 4 + 16);    // LDS of the matrix-core logits kernel: the staged output tile
+                                                          // (the two token stages fit inside)
+
 // Matrix-core path: token tile height (in 16-row blocks) and H split.
 struct MfmaGrid { bool use; int tb, tiles_t, tiles_e, splits, k_per_split; };
 
@@ -778,27 +781,15 @@ int launch_route(const moe_config &c, const void *x, const float *x_scale, const
         const dim3 grid(m.tiles_t * m.splits, m.tiles_e, 1);
         if (c.dtype == MOE_DTYPE_FP8_E4M3) {
             auto kern = router_logits_mfma_kernel<true, 8>;
-            constexpr int lds = 8 * 16 * (RM_BE * 4 + 16);   // the staged output tile (the two token stages fit inside)
-            static bool attr_done = false;
-            if (!attr_done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-                if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
-                attr_done = true;
-            }
-            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, router_w, zpart, c.T, c.H, c.E,
+            static DeviceOnce lds_limit_set;
+            if ((rc = set_dynamic_lds(lds_limit_set, reinterpret_cast<const void *>(kern), RM_OUT_LDS)) != MOE_OK) return rc;
+            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), RM_OUT_LDS, s, x, x_scale, router_w, zpart, c.T, c.H, c.E,
                                m.k_per_split, m.splits);
         } else {
             auto kern = router_logits_mfma_kernel<false, 8>;
-            constexpr int lds = 8 * 16 * (RM_BE * 4 + 16);   // the staged output tile (the two token stages fit inside)
-            static bool attr_done = false;
-            if (!attr_done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-                if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
-                attr_done = true;
-            }
-            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), lds, s, x, x_scale, router_w, zpart, c.T, c.H, c.E,
+            static DeviceOnce lds_limit_set;
+            if ((rc = set_dynamic_lds(lds_limit_set, reinterpret_cast<const void *>(kern), RM_OUT_LDS)) != MOE_OK) return rc;
+            hipLaunchKernelGGL(kern, grid, dim3(RM_THREADS), RM_OUT_LDS, s, x, x_scale, router_w, zpart, c.T, c.H, c.E,
                                m.k_per_split, m.splits);
         }
         rc = check_launch();

@@ -9,7 +9,7 @@ from oracle import moe_oracle as orc
 # Tolerances of the layer output (bf16 path / fp8 path), relative to max|ref| and as
 # mean relative error sum|err| / sum|ref|.
 TOL_MAX = {False: 2e-2, True: 6e-2}
-TOL_MEAN = {False: 5e-3, True: 5e-2}
+TOL_MEAN = {False: 5e-3, True: 3e-2}
 TIE_MARGIN = 1e-6           # routing decisions closer than this may legitimately differ
 
 

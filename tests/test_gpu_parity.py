@@ -62,6 +62,22 @@ CASES = {
     "router_deep_fp8": syn.Workload("router_deep_fp8", T=1300, H=1920, I=128, E=132, top_k=4, fp8=True),
     # the limits of the interface: 512 experts (8 per lane in the router) and 64 experts per token
     "max_experts": syn.Workload("max_experts", T=40, H=128, I=64, E=512, top_k=64),
+    # fp8 contractions longer than 64 scale blocks (a slab's weight scales fill a second register per
+    # lane): 66 blocks along H, and 96 along I with a row stride that is a multiple of 4 KiB (the K
+    # loops of neighbouring workgroups then start at different columns)
+    "fp8_deep_h": syn.Workload("fp8_deep_h", T=24, H=8448, I=128, E=4, top_k=2, fp8=True),
+    "fp8_deep_i": syn.Workload("fp8_deep_i", T=24, H=128, I=12288, E=4, top_k=2, fp8=True),
+    # the wide (8-wavefront) bf16 workgroups of the benchmark shapes, reached by making one GEMM
+    # dimension long while the oracle's work stays small:
+    #   gate/up, 128-row tiles, one tile per work range, a ragged last round handed out as half-width items
+    "wide128_gateup_halves": syn.Workload("wide128_gateup_halves", T=300, H=128, I=9216, E=8, top_k=2),
+    #   gate/up, 256-row tiles, every expert cut into two tiles
+    "wide256_gateup_split": syn.Workload("wide256_gateup_split", T=700, H=128, I=16384, E=4, top_k=2),
+    #   down projection, 256-row tiles, every expert cut into two tiles (which share their weights through L2)
+    "wide256_down_split": syn.Workload("wide256_down_split", T=700, H=32768, I=128, E=4, top_k=2),
+    #   more than 64 tiles of up to 16 row blocks: both GEMMs wide, work cut into equal parts and
+    #   walked alternating between tall and short tiles
+    "wide256_zigzag": syn.Workload("wide256_zigzag", T=2800, H=1024, I=512, E=128, top_k=8),
 }
 
 

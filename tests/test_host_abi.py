@@ -33,6 +33,16 @@ def test_every_declared_symbol_is_exported(lib):
         assert getattr(lib, n) is not None
 
 
+def test_nothing_but_the_c_abi_is_exported(lib):
+    """The dynamic symbol table holds the declared entry points and nothing else of ours (the
+    toolchain's own per-translation-unit markers aside)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", moe.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    syms = [line.split()[-1] for line in out.splitlines() if line.strip()]
+    ours = [s for s in syms if not s.startswith("__hip_")]
+    assert sorted(ours) == sorted(moe.EXPORTS), sorted(set(ours) ^ set(moe.EXPORTS))
+
+
 def test_config_struct_matches_header():
     text = open(os.path.join(ROOT, "include", "moe.h")).read()
     body = re.search(r"typedef struct moe_config \{(.*?)\} moe_config;", text, flags=re.S).group(1)
@@ -76,6 +86,8 @@ def test_size_queries_and_tile_heights(lib):
     (dict(num_local_experts=-1), -1),
     (dict(quantize_x=1), -1),                                           # quantise-on-the-path needs an fp8 layer
     (dict(quantize_x=2, dtype=1), -1),
+    (dict(dtype=1, H=16384 + 128), -2),                                 # fp8: more than 128 scale blocks along H
+    (dict(dtype=1, I=16384 + 128), -2),
 ])
 def test_bad_problem_statements_are_refused(lib, change, code):
     cfg = moe.MoEConfig(T=16, H=256, I=128, E=8, top_k=2, scoring=0, renormalize=1, n_group=1,
