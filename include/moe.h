@@ -232,6 +232,28 @@ MOE_API int moe_forward_marked(const moe_config *cfg, const void *x, const float
                        const float *w2_scale, void *out, void *workspace, size_t workspace_bytes,
                        void *stream, void *const *events);
 
+/*
+ * moe_forward for callers that cannot allocate device memory or pass a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * intermediates live in a buffer the library itself holds on every device it runs on
+ * (MOE_STATIC_SCRATCH_BYTES, static device memory, kept until the process ends); the call
+ * allocates and frees nothing, on the host or the device.  Same kernels, same results, bit for
+ * bit, as moe_forward.
+ *   - A problem whose moe_workspace_size(cfg) exceeds MOE_STATIC_SCRATCH_BYTES is refused with
+ *     MOE_ERR_WORKSPACE before anything is enqueued (the benchmark-sized decode and Mixtral-shaped
+ *     layers fit; the 4096-token DeepSeek-shaped prefill does not: use moe_forward there).
+ *   - All calls on one device share that buffer: two such calls must not overlap on the device
+ *     (put them on one stream, or order the streams); overlapping calls race.  Nothing in the
+ *     buffer has to start at zero and nothing is kept from one call to the next.
+ *   - The buffer's address is looked up on the first call on a device; moe_init() does the same
+ *     lookup for the current device ahead of time (call it before a graph capture starts).
+ */
+enum { MOE_STATIC_SCRATCH_BYTES = 64 << 20 };
+MOE_API int moe_init(void);
+MOE_API int moe_forward_static(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+                               const float *bias, const void *w1, const float *w1_scale, const void *w2,
+                               const float *w2_scale, void *out, void *stream);
+
 /* Text for an error code; the hipError_t of the last failed launch on this thread. */
 MOE_API const char *moe_error_string(int code);
 MOE_API int moe_last_hip_error(void);

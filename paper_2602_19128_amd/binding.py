@@ -18,8 +18,10 @@ LIB_PATH = os.path.join(_PKG, "libmoe_gfx950.so")
 EXPORTS = [
     "moe_tile_rows", "moe_max_tiles", "moe_route_workspace_size", "moe_workspace_size",
     "moe_route", "moe_quantize_act", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm_down",
-    "moe_combine", "moe_forward", "moe_forward_marked", "moe_error_string", "moe_last_hip_error",
+    "moe_combine", "moe_forward", "moe_forward_marked", "moe_init", "moe_forward_static",
+    "moe_error_string", "moe_last_hip_error",
 ]
+STATIC_SCRATCH_BYTES = 64 << 20   # MOE_STATIC_SCRATCH_BYTES
 
 TILE_INTS = 8            # int32 fields of one moe_tile record
 SCHED_INTS = 16          # int32 entries of the schedule header moe_permute writes (MOE_SCHED_INTS)
@@ -94,6 +96,10 @@ def load():
     lib.moe_forward.argtypes = [cfgp, vp, f32p, f32p, f32p, vp, f32p, vp, f32p, vp, vp, C.c_size_t, vp]
     lib.moe_forward_marked.restype = C.c_int
     lib.moe_forward_marked.argtypes = lib.moe_forward.argtypes + [C.POINTER(C.c_void_p)]
+    lib.moe_init.restype = C.c_int
+    lib.moe_init.argtypes = []
+    lib.moe_forward_static.restype = C.c_int
+    lib.moe_forward_static.argtypes = [cfgp, vp, f32p, f32p, f32p, vp, f32p, vp, f32p, vp, vp]
     lib.moe_error_string.restype = C.c_char_p
     lib.moe_error_string.argtypes = [C.c_int]
     lib.moe_last_hip_error.restype = C.c_int
@@ -255,6 +261,20 @@ def moe_forward(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out
     else:
         rc = load().moe_forward_marked(*args, events)
     _check(rc, "moe_forward")
+    return out
+
+
+def moe_init():
+    _check(load().moe_init(), "moe_init")
+
+
+def moe_forward_static(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out):
+    """moe_forward on the library's own static scratch: `out` is the caller's, nothing is allocated."""
+    _expect(x, (cfg.T, cfg.H), _x_arrives_as(cfg), "x")
+    _expect(out, (cfg.T, cfg.H), torch.bfloat16, "out")
+    rc = load().moe_forward_static(C.byref(cfg), _p(x), _p(x_scale), _p(router_w), _p(bias), _p(w1), _p(w1_scale),
+                                   _p(w2), _p(w2_scale), _p(out), _stream())
+    _check(rc, "moe_forward_static")
     return out
 
 

@@ -103,6 +103,31 @@ Layout layout_for(const moe_config &c)
 
 bool fp8(const moe_config *c) { return c->dtype == MOE_DTYPE_FP8_E4M3; }
 
+// Library-owned workspace of moe_forward_static: one array per device, held until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; what kernels and copies get
+// is the per-device address looked up below.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
+
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Address of `scratch` on the current device (looked up once per device; the lookup is idempotent, so
+// two threads racing through it store the same value).
+int static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
+    if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) { set_last_hip_error(e); return MOE_ERR_HIP; }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return MOE_OK;
+}
+
 }  // namespace
 }  // namespace moe
 
@@ -260,13 +285,33 @@ int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, cons
                               workspace_bytes, stream, nullptr);
 }
 
+int moe_init(void)
+{
+    void *p = nullptr;
+    return static_scratch(&p);
+}
+
+int moe_forward_static(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,
+                       const float *bias, const void *w1, const float *w1_scale, const void *w2,
+                       const float *w2_scale, void *out, void *stream)
+{
+    int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (cfg->T == 0) return MOE_OK;
+    if (layout_for(*cfg).total > (size_t)MOE_STATIC_SCRATCH_BYTES) return MOE_ERR_WORKSPACE;   // before anything touches the device
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != MOE_OK) return rc;
+    return moe_forward_marked(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out, ws,
+                              (size_t)MOE_STATIC_SCRATCH_BYTES, stream, nullptr);
+}
+
 const char *moe_error_string(int code)
 {
     switch (code) {
     case MOE_OK: return "ok";
     case MOE_ERR_INVALID: return "invalid argument";
     case MOE_ERR_UNSUPPORTED: return "unsupported shape or dtype";
-    case MOE_ERR_WORKSPACE: return "workspace too small";
+    case MOE_ERR_WORKSPACE: return "workspace too small (moe_forward_static: the problem needs more than the static scratch)";
     case MOE_ERR_HIP: return "HIP launch failed";
     default: return "unknown error";
     }

@@ -112,8 +112,25 @@ def test_null_pointers_and_small_workspace_are_refused(lib):
     rc = lib.moe_forward(C.byref(cfg), one, None, one, None, one, None, one, None, one, C.c_void_p(264),
                          C.c_size_t(1 << 40), None)
     assert rc == -1                      # workspace not 256-byte aligned
-    assert lib.moe_error_string(-3) == b"workspace too small"
+    assert lib.moe_error_string(-3).startswith(b"workspace too small")
     assert lib.moe_forward(None, one, None, one, None, one, None, one, None, one, one, C.c_size_t(0), None) == -1
+
+
+def test_static_scratch_entry_refuses_large_problems_without_touching_the_device(lib):
+    """moe_forward_static: a problem beyond the static scratch is refused on the host, before any
+    device call (so this runs without a GPU); a bad problem statement gets its usual code."""
+    one = C.c_void_p(256)
+    big = moe.MoEConfig.from_workload(syn.WORKLOADS["dsv3_prefill"])
+    assert moe.moe_workspace_size(big) > moe.STATIC_SCRATCH_BYTES
+    assert lib.moe_forward_static(C.byref(big), one, None, one, one, one, None, one, None, one, None) == -3
+    for name in ("tiny", "mixtral_prefill", "dsv3_decode"):
+        assert moe.moe_workspace_size(moe.MoEConfig.from_workload(syn.WORKLOADS[name])) <= moe.STATIC_SCRATCH_BYTES
+    bad = moe.MoEConfig(T=16, H=100, I=128, E=8, top_k=2)
+    assert lib.moe_forward_static(C.byref(bad), one, None, one, None, one, None, one, None, one, None) == -2
+    none = moe.MoEConfig(T=0, H=256, I=128, E=8, top_k=2, renormalize=1)
+    assert lib.moe_forward_static(C.byref(none), None, None, None, None, None, None, None, None, None, None) == 0
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    assert int(re.search(r"MOE_STATIC_SCRATCH_BYTES = (\d+) << 20", text).group(1)) << 20 == moe.STATIC_SCRATCH_BYTES
 
 
 def test_quantise_on_the_path_sizes_and_argument_checks(lib):
