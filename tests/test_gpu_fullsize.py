@@ -2,9 +2,13 @@
 (one moe_forward call on a preallocated workspace).
 
 The oracle cannot run these sizes in full, so: routing and the sort-scatter are
-compared for every token (they need no expert weights), and the layer output is
-compared on a seeded sample of tokens the oracle computes one by one.  Tensors
-are drawn on the GPU and copied to the host for the oracle.
+compared for every token (they need no expert weights); both grouped GEMMs are
+compared on rows taken from EVERY tile of the schedule the launch really ran
+(first row, last row and two seeded rows of each tile, every column of those rows,
+so that each tile height, each ragged last row block, each tile of a split expert
+and every column slab is looked at); and the layer output is compared on a seeded
+sample of tokens the oracle computes one by one.  Tensors are drawn on the GPU
+and copied to the host for the oracle.
 """
 import numpy as np
 import pytest
@@ -18,7 +22,8 @@ from parity_util import (TOL_MAX, TOL_MEAN, check_tiles, choice_keys, compare_ro
 
 pytestmark = pytest.mark.gpu
 
-SAMPLE_TOKENS = 24
+SAMPLE_TOKENS = 96
+ROWS_PER_TILE = 4           # first, last and two seeded rows of every tile
 
 
 def _check_workload(gpu, host_w, sample_tokens=SAMPLE_TOKENS):
@@ -56,6 +61,43 @@ def _check_workload(gpu, host_w, sample_tokens=SAMPLE_TOKENS):
     load = np.diff(off_r)
     print(f"  routing: tie-excused tokens={other} swapped slots={swapped} of {wl.T}; "
           f"active experts={(load > 0).sum()} max/mean load={load.max() / load.mean():.2f}", flush=True)
+
+    # both GEMMs on rows of every tile of this schedule, every column of those rows
+    n_tiles = int(sched.cpu()[0])
+    rec = tiles.cpu().numpy()[:n_tiles]
+    rng_t = np.random.default_rng(1)
+    rows = []
+    for _, row0, nrows, _first, _count, *_pad in rec:
+        inner = rng_t.integers(0, nrows, size=ROWS_PER_TILE - 2)
+        rows += [row0, row0 + nrows - 1] + [row0 + int(r) for r in inner]
+    rows = np.unique(np.asarray(rows, dtype=np.int64))
+    pair = sp_r[rows]                                        # sorted row -> pair id
+    tok = (pair // wl.top_k).astype(np.int32)
+    exp = (ids_g.cpu().numpy().reshape(-1)[pair] - wl.local_offset).astype(np.int32)
+    x_g, xs_g = (gpu.x, gpu.x_scale)
+    if wl.quantize_x:
+        x_g, xs_g = moe.moe_quantize_act(cfg, gpu.x)
+    act_g, asc_g = moe.moe_grouped_gemm_swiglu(cfg, x_g, xs_g, gpu.w1, gpu.w1_scale, sp_g, tiles, sched)
+    y_g = moe.moe_grouped_gemm_down(cfg, act_g, asc_g, gpu.w2, gpu.w2_scale, tiles, sched)
+    torch.cuda.synchronize()
+    pick = torch.from_numpy(rows).cuda()
+    act_rows = f64(act_g[pick])
+    if asc_g is not None:
+        act_rows = act_rows * np.repeat(f64(asc_g[pick]), 128, axis=1)
+    act_ref = orc.swiglu_rows(p, tok, exp)
+    a_max, a_mean = err_stats(act_rows, act_ref)
+    y_ref = orc.down_rows(p, exp, act_rows)                  # from the activations the GPU consumed
+    y_max, y_mean = err_stats(f64(y_g[pick]), y_ref)
+    heights = sorted(set(int(-(-r // 16)) for r in rec[:, 2]))
+    print(f"  staged GEMMs: {len(rows)} rows of {n_tiles} tiles ({len(set(rec[:, 0]))} experts, "
+          f"{int((rec[:, 4] > 1).sum())} tiles of split experts, row blocks per tile {heights[0]}..{heights[-1]}): "
+          f"act max_rel={a_max:.2e} mean_rel={a_mean:.2e}; y max_rel={y_max:.2e} mean_rel={y_mean:.2e}", flush=True)
+    if wl.fp8:
+        assert a_max <= 2 ** -4 + 1e-3 and a_mean <= 3.5e-2  # e4m3 re-quantisation of act (3 mantissa bits)
+    else:
+        assert a_max <= 6e-3 and a_mean <= 3e-3              # one bf16 rounding of an fp32 accumulation
+    assert y_max <= 6e-3 and y_mean <= 3e-3
+    del act_g, asc_g, y_g
 
     # layer output on sampled tokens
     rng = np.random.default_rng(0)
