@@ -127,6 +127,33 @@ def measure(wl, inp, host, K, W, cpu_seconds, graph, seed, log, min_warm_ms=0.0)
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
 
+    # the same K forwards without the step events (recording five events per call costs a few
+    # microseconds each, which is most of a latency-bound layer), and - where the library offers it
+    # for this problem - as one persistent launch instead of the pipeline
+    plain = moe.PreparedForward(cfg, inp.x, inp.x_scale, inp.router_w, inp.bias, inp.w1, inp.w1_scale, inp.w2,
+                                inp.w2_scale, out, ws)
+
+    def unmarked():
+        for _ in range(max(W, 20)):
+            plain()
+        torch.cuda.synchronize()
+        u0 = time.perf_counter()
+        for _ in range(K):
+            plain()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - u0) * 1e6 / K
+
+    unmarked_us = unmarked()
+    single_us = None
+    moe.moe_single_launch(True)
+    try:
+        if moe.moe_single_launch_mode(cfg) == moe.SINGLE_LAUNCH_ALL:
+            pipeline_bits = out.clone()
+            single_us = unmarked()
+            assert torch.equal(out.view(torch.int16), pipeline_bits.view(torch.int16)), "single launch changed the output"
+    finally:
+        moe.moe_single_launch(False)
+
     # supplementary: the same call recorded into a HIP graph and replayed (the library neither
     # allocates nor synchronises, so it can be captured)
     graph_us = None
@@ -242,7 +269,8 @@ def measure(wl, inp, host, K, W, cpu_seconds, graph, seed, log, min_warm_ms=0.0)
         "tflops": round(tflops, 1), "frac_mfma_peak": round(tflops / PEAK_MFMA_TFLOPS[kind], 4),
         "gbps": round(gbps, 1), "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
         "roofline_time_us": round(ideal_us, 1), "frac_of_roofline": round(ideal_us / (ms_per_step * 1e3), 4),
-        "gpu_event_us": round(gpu_ms * 1e3, 2),
+        "gpu_event_us": round(gpu_ms * 1e3, 2), "unmarked_us": round(unmarked_us, 2),
+        "single_launch_us": None if single_us is None else round(single_us, 2),
         "graph_replay_us": None if graph_us is None else round(graph_us, 2),
         "step_us": {n_: round(v * 1e3, 2) for n_, v in step_ms.items()},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_sample": parity,
@@ -253,12 +281,14 @@ def compact(rec):
     """The nested form of a workload's record: the same measurements, fewer words."""
     r = rec["roofline"]
     c = rec["config"]
-    out = {"us": rec["value"], "roofline_us": rec["roofline_time_us"], "frac_of_roofline": rec["frac_of_roofline"],
+    out = {"us": rec["value"], "unmarked_us": rec["unmarked_us"], "roofline_us": rec["roofline_time_us"], "frac_of_roofline": rec["frac_of_roofline"],
            "dtype": rec["dtype"], "T": c["T"], "pairs": c["routed_pairs"], "active_experts": c["active_experts"],
            "load_max_over_mean": c["max_over_mean_load"], "tflops": rec["tflops"], "frac_mfma": rec["frac_mfma_peak"],
            "gbps": rec["gbps"], "frac_hbm": rec["frac_hbm_peak"], "step_us": rec["step_us"],
            "gate_up": {"gbps": r["achieved"], "frac": r["frac"]},
            "down": {"gbps": r["down_gemm"]["achieved"], "frac": r["down_gemm"]["frac"]}}
+    if rec["single_launch_us"] is not None:
+        out["single_launch_us"] = rec["single_launch_us"]
     if rec["cpu_baseline"]:
         out["cpu_oracle_us"] = rec["cpu_baseline"]["value"]
         out["cpu_sample"] = rec["cpu_baseline"]["sample"].split(" (")[0] + (" (sampled)" if "sampled" in rec["cpu_baseline"]["sample"] else " (all)")
@@ -356,7 +386,7 @@ def main():
         "data": "synthetic",
     }
     for key in ("config", "tflops", "frac_mfma_peak", "gbps", "frac_hbm_peak", "roofline_time_us", "frac_of_roofline",
-                "gpu_event_us", "graph_replay_us", "step_us", "roofline", "cpu_baseline", "parity_sample"):
+                "gpu_event_us", "unmarked_us", "single_launch_us", "graph_replay_us", "step_us", "roofline", "cpu_baseline", "parity_sample"):
         line[key] = rec[key]
     if len(names) > 1:
         line["workloads"] = {n: compact(records[n]) for n in names[1:]}

@@ -219,12 +219,42 @@ MOE_API int moe_forward(const moe_config *cfg, const void *x, const float *x_sca
                 void *stream);
 
 /*
+ * Latency-bound problems in one launch (paper Sec. 4.5 weighs one persistent kernel against a
+ * pipeline of several launches and finds the pipeline faster; so it is here, see below).  When
+ * switched on, moe_forward runs small bf16 problems - at most 1024 (token, slot) pairs, at most
+ * 256 experts, row tiles of at most 64 rows and expert matrices small enough that the narrow GEMM
+ * workgroups are used - as ONE persistent kernel instead of one kernel per step.  Its phases run the
+ * same device code as the stand-alone kernels and give the same bits in the output and in every
+ * intermediate of the workspace; they are separated by grid-wide barriers on counters in
+ * library-owned device memory, so two such launches must not overlap on one device (launches on one
+ * stream never do).  Waits are bounded: see moe_single_launch_timeouts.
+ * Off by default: back to back on one stream the pipeline's launches overlap with its kernels and it
+ * is the faster of the two on the device (16 tokens, 8 experts of 256 x 128: 21 us against 25 us per
+ * layer); the single launch costs the calling thread a quarter of the time (4 us against 18 us per
+ * layer), which is what a host-bound caller buys with it.
+ *   moe_single_launch(enable)       process-wide switch
+ *   moe_single_launch_mode(cfg)     MOE_SINGLE_LAUNCH_ALL if moe_forward would run cfg as one launch
+ *                                   right now, else MOE_SINGLE_LAUNCH_NONE (negative: error code)
+ *   moe_single_launch_timeouts(&n)  barrier waits given up on the current device since the library was
+ *                                   loaded (0 unless the device was so busy with other work that a
+ *                                   launch could not become resident within about two seconds; the
+ *                                   output of such a launch is undefined).  Copies from the device: it
+ *                                   synchronises with the device's work.
+ */
+enum { MOE_SINGLE_LAUNCH_NONE = 0, MOE_SINGLE_LAUNCH_ALL = 1 };
+MOE_API void moe_single_launch(int enable);
+MOE_API int moe_single_launch_mode(const moe_config *cfg);
+MOE_API int moe_single_launch_timeouts(uint32_t *count_out /* HOST */);
+
+/*
  * moe_forward with step boundaries marked for timing: `events` is a HOST array of
  * MOE_FORWARD_EVENTS hipEvent_t handles (created by the caller) that are recorded
  * on `stream` before routing and after each of the five steps, in pipeline order
  * (route, sort-scatter, gate/up GEMM, down GEMM, combine; with cfg->quantize_x the
  * quantisation of x is inside the first interval).  The kernels and their
- * launch configuration are exactly those of moe_forward.
+ * launch configuration are exactly those of moe_forward; where one launch covers all the
+ * steps (see moe_single_launch) their events are all recorded after it, so the first
+ * interval holds the whole launch and the others are empty.
  */
 enum { MOE_FORWARD_EVENTS = 6 };
 MOE_API int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scale, const float *router_w,

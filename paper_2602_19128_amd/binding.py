@@ -19,6 +19,7 @@ EXPORTS = [
     "moe_tile_rows", "moe_max_tiles", "moe_route_workspace_size", "moe_workspace_size",
     "moe_route", "moe_quantize_act", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm_down",
     "moe_combine", "moe_forward", "moe_forward_marked", "moe_init", "moe_forward_static",
+    "moe_single_launch", "moe_single_launch_mode", "moe_single_launch_timeouts",
     "moe_error_string", "moe_last_hip_error",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20   # MOE_STATIC_SCRATCH_BYTES
@@ -100,6 +101,12 @@ def load():
     lib.moe_init.argtypes = []
     lib.moe_forward_static.restype = C.c_int
     lib.moe_forward_static.argtypes = [cfgp, vp, f32p, f32p, f32p, vp, f32p, vp, f32p, vp, vp]
+    lib.moe_single_launch.restype = None
+    lib.moe_single_launch.argtypes = [C.c_int]
+    lib.moe_single_launch_mode.restype = C.c_int
+    lib.moe_single_launch_mode.argtypes = [cfgp]
+    lib.moe_single_launch_timeouts.restype = C.c_int
+    lib.moe_single_launch_timeouts.argtypes = [C.POINTER(C.c_uint32)]
     lib.moe_error_string.restype = C.c_char_p
     lib.moe_error_string.argtypes = [C.c_int]
     lib.moe_last_hip_error.restype = C.c_int
@@ -264,6 +271,26 @@ def moe_forward(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out
     return out
 
 
+SINGLE_LAUNCH_NONE, SINGLE_LAUNCH_ALL = 0, 1
+
+
+def moe_single_launch(enable: bool):
+    load().moe_single_launch(1 if enable else 0)
+
+
+def moe_single_launch_mode(cfg) -> int:
+    rc = int(load().moe_single_launch_mode(C.byref(cfg)))
+    if rc < 0:
+        _check(rc, "moe_single_launch_mode")
+    return rc
+
+
+def moe_single_launch_timeouts() -> int:
+    n = C.c_uint32(0)
+    _check(load().moe_single_launch_timeouts(C.byref(n)), "moe_single_launch_timeouts")
+    return int(n.value)
+
+
 def moe_init():
     _check(load().moe_init(), "moe_init")
 
@@ -276,6 +303,24 @@ def moe_forward_static(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_sca
                                    _p(w2), _p(w2_scale), _p(out), _stream())
     _check(rc, "moe_forward_static")
     return out
+
+
+class PreparedForward:
+    """moe_forward with its arguments marshalled once (for loops where the marshalling would be most
+    of the host time of a call); the stream is the one current when it was prepared."""
+
+    def __init__(self, cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out, workspace):
+        _expect(x, (cfg.T, cfg.H), _x_arrives_as(cfg), "x")
+        _expect(out, (cfg.T, cfg.H), torch.bfloat16, "out")
+        self._keep = (cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out, workspace)
+        self._fn = load().moe_forward
+        self._args = (C.byref(cfg), _p(x), _p(x_scale), _p(router_w), _p(bias), _p(w1), _p(w1_scale), _p(w2),
+                      _p(w2_scale), _p(out), _p(workspace), C.c_size_t(workspace.numel()), _stream())
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != 0:
+            _check(rc, "moe_forward")
 
 
 def forward_inputs(inp, out=None, workspace=None):

@@ -253,6 +253,12 @@ int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scal
     };
 
     if ((rc = mark()) != MOE_OK) return rc;
+    if (single_launch_mode(*cfg, tr) == MOE_SINGLE_LAUNCH_ALL) {
+        rc = launch_fused(*cfg, tr, mt, x, router_w, bias, ws + l.route, ids, w, offsets, sorted_pair, inv, tiles,
+                          sched, w1, w2, act, y, out, s);
+        for (int i = 0; rc == MOE_OK && i < 5; ++i) rc = mark();   // the one launch has done all five steps
+        return rc;
+    }
     const void *x_route = x;                                  // what the router scores
     const float *x_route_scale = x_scale;
     if (cfg->quantize_x) {
@@ -283,6 +289,24 @@ int moe_forward(const moe_config *cfg, const void *x, const float *x_scale, cons
 {
     return moe_forward_marked(cfg, x, x_scale, router_w, bias, w1, w1_scale, w2, w2_scale, out, workspace,
                               workspace_bytes, stream, nullptr);
+}
+
+void moe_single_launch(int enable) { set_single_launch(enable); }
+
+int moe_single_launch_mode(const moe_config *cfg)
+{
+    const int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    return single_launch_mode(*cfg, tile_rows_for(*cfg));
+}
+
+int moe_single_launch_timeouts(uint32_t *count_out)
+{
+    if (!count_out) return MOE_ERR_INVALID;
+    unsigned n = 0;
+    const int rc = single_launch_timeouts(&n);
+    *count_out = n;
+    return rc;
 }
 
 int moe_init(void)

@@ -1,13 +1,5 @@
-// Weighted combine: out[t,:] = sum_j w[t,j] * y[inv[t*k+j],:].
-//
-// Each thread owns 8 consecutive hidden elements of one token and walks the token's
-// k expert rows in slot order (their loads requested eight at a time), so the fp32 sum
-// has one fixed order and needs no atomics; the result is rounded once to bf16
-// (nearest-even).  NT: the expert rows are read with non-temporal loads - right when [P,H] is far
-// larger than the L2s and was streamed out by the down projection (4096 DeepSeek tokens: 103 ->
-// 80 us); wrong when only a share of the experts is local and the few rows that exist are still
-// cached (measured 24 -> 29 us on a 32-of-256 share), so the launch picks.
-#include "moe_internal.hpp"
+// Weighted combine kernel; the arithmetic is in moe_combine_device.hpp.
+#include "moe_combine_device.hpp"
 
 namespace moe {
 namespace {
@@ -18,53 +10,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t *__restrict
                                                       const int32_t *__restrict__ inv,
                                                       uint16_t *__restrict__ out, int T, int H, int k)
 {
-    const int chunks = H / 8;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long long)T * chunks) return;
-    const int t = (int)(idx / chunks), h = (int)(idx % chunks) * 8;
-    float acc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    // slots in groups of CB: the rows of a group are requested together, then added in slot order
-    constexpr int CB = 8;
-    for (int j0 = 0; j0 < k; j0 += CB) {
-        int row[CB];
-        float wt[CB];
-        uint4 raw[CB];
-#pragma unroll
-        for (int u = 0; u < CB; ++u) {
-            const bool in = j0 + u < k;
-            row[u] = in ? inv[(size_t)t * k + j0 + u] : -1;
-            wt[u] = in ? w[(size_t)t * k + j0 + u] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < CB; ++u)
-        {
-            typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (row[u] >= 0) {
-                const u32x4_t *src = reinterpret_cast<const u32x4_t *>(y + (size_t)row[u] * H + h);
-                v = NT ? __builtin_nontemporal_load(src) : *src;
-            }
-            raw[u] = uint4{v[0], v[1], v[2], v[3]};
-        }
-#pragma unroll
-        for (int u = 0; u < CB; ++u) {
-            if (row[u] < 0) continue;                      // a pair without a row (its expert is held elsewhere)
-            const uint32_t v[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc[2 * i] = fmaf(wt[u], bf16_bits_to_f32(v[i] & 0xffffu), acc[2 * i]);
-                acc[2 * i + 1] = fmaf(wt[u], bf16_bits_to_f32(v[i] >> 16), acc[2 * i + 1]);
-            }
-        }
-    }
-    uint4 o;
-    o.x = pack_bf16x2(acc[0], acc[1]);
-    o.y = pack_bf16x2(acc[2], acc[3]);
-    o.z = pack_bf16x2(acc[4], acc[5]);
-    o.w = pack_bf16x2(acc[6], acc[7]);
-    *reinterpret_cast<uint4 *>(out + (size_t)t * H + h) = o;
+    if (idx >= (long long)T * (H / 8)) return;
+    combine_chunk<NT>(y, w, inv, out, H, k, idx);
 }
 
 }  // namespace
@@ -74,7 +22,7 @@ int launch_combine(const moe_config &c, const void *y, const float *w, const int
 {
     const long long work = (long long)c.T * (c.H / 8);
     const unsigned blocks = (unsigned)((work + 255) / 256);
-    const bool streamed = local_experts(c) == c.E && (size_t)c.T * c.top_k * c.H * 2 > ((size_t)32 << 20);
+    const bool streamed = combine_streams(c);
     if (streamed)
         hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(256), 0, s, static_cast<const uint16_t *>(y), w, inv,
                            static_cast<uint16_t *>(out), c.T, c.H, c.top_k);

@@ -540,13 +540,14 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
 //     tiles per XCD equal item counts are what lets the XCDs finish together.
 // The launch normally has one workgroup per item; the loop only matters when a part holds more
 // work than its share of the grid.
+// Workgroup `block` of `nblocks` (a multiple of MOE_WORK_RANGES) works through its share of the
+// schedule; the stand-alone kernel below and the single-launch forward both run this loop.
 template <class SH>
-__global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
-                                                                   const int32_t *__restrict__ sched, int col_tiles,
-                                                                   int whole_ranges, int round_slots)
+__device__ __forceinline__ void gemm_items(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
+                                           int col_tiles, int whole_ranges, int round_slots, int block, int nblocks,
+                                           unsigned char *smem)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int part = blockIdx.x % MOE_WORK_RANGES;
+    const int part = block % MOE_WORK_RANGES;
     int first, items;
     if (whole_ranges) {
         first = sched[1 + part] * col_tiles;
@@ -557,7 +558,7 @@ __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, c
         first = part * per;
         items = min(per, total - first);
     }
-    const int stride = gridDim.x / MOE_WORK_RANGES;
+    const int stride = nblocks / MOE_WORK_RANGES;
     // Order inside a long part: alternating between its front and its back in chunks of col_tiles
     // items (tall tile, short tile, tall, ...) instead of tallest-first.  Tall tiles spend their
     // time on LDS and the matrix cores, short ones on the weight stream, and a mix of both running
@@ -572,7 +573,7 @@ __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, c
     const int rest = items % round_slots;
     const int halved = (SH::HALF_ITEMS && whole_ranges && rest > 0 && 2 * rest <= round_slots) ? rest : 0;
     const int slots = zigzag ? nchunks * col_tiles : items + halved;
-    for (int slot = blockIdx.x / MOE_WORK_RANGES; slot < slots; slot += stride) {
+    for (int slot = block / MOE_WORK_RANGES; slot < slots; slot += stride) {
         int pos = slot;
         if (zigzag) {
             const int c = slot / col_tiles;
@@ -597,6 +598,16 @@ __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, c
     }
 }
 
+
+template <class SH>
+__global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
+                                                                   const int32_t *__restrict__ sched, int col_tiles,
+                                                                   int whole_ranges, int round_slots)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    gemm_items<SH>(g, tiles, sched, col_tiles, whole_ranges, round_slots, (int)blockIdx.x, (int)gridDim.x, smem);
+}
+
 template <class SH>
 int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched, int max_tiles, int est_tiles,
                  hipStream_t s)
@@ -618,32 +629,33 @@ int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
     return check_launch();
 }
 
-// Narrow (4-wavefront) workgroups when the wide ones would leave compute units without work
-// (not for the fp8 gate/up GEMM, whose epilogue needs a whole 128-column block per workgroup).
+// The workgroup widths (see gemm_width) as kernel shapes.
+template <int MB_MAX, bool SWIGLU, bool FP8>
+struct ShapesFor {
+    static constexpr int DA = MB_MAX >= 16 ? 1 : 2;           // 16 row blocks: 32 KiB per token stage
+    static constexpr int DW = 2;
+    using Wide = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8>;
+    using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU, FP8>;
+    using Wide4 = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8, SWIGLU ? 2 : 4>;
+};
+
 template <int MB_MAX, bool SWIGLU, bool FP8>
 int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched, int max_tiles, int est_tiles,
                     hipStream_t s)
 {
-    constexpr int DA = MB_MAX >= 16 ? 1 : 2;                  // 16 row blocks: 32 KiB per token stage
-    constexpr int DW = 2;
-    // Down projection of low tiles (32 or 64 rows): four weight blocks per wavefront, i.e. 512
-    // output columns per workgroup.  Its K loop is short (16 steps for fp8 with I = 2048), so the
-    // fixed cost of a workgroup is a third of its life, and the accumulators of a low tile leave the
-    // registers for it: half as many workgroups, each token fragment feeds four MFMAs instead of
-    // two (fp8 prefill: down GEMM -4 %).  Not for 16-row tiles, where two workgroups per compute
-    // unit already overlap those costs (the decode shape measured +0.5 %).
-    if constexpr (!SWIGLU && (MB_MAX == 2 || MB_MAX == 4)) {
-        using Wide4 = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8, 4>;
-        if ((long)est_tiles * ceil_div(g.n_out, Wide4::COLS) >= 4 * GM_CUS)
-            return launch_shape<Wide4>(g, tiles, sched, max_tiles, est_tiles, s);
+    using SF = ShapesFor<MB_MAX, SWIGLU, FP8>;
+    switch (gemm_width(MB_MAX, SWIGLU, FP8, g.n_out, est_tiles)) {
+    case GEMM_WIDE4:
+        if constexpr (!SWIGLU && (MB_MAX == 2 || MB_MAX == 4))
+            return launch_shape<typename SF::Wide4>(g, tiles, sched, max_tiles, est_tiles, s);
+        return MOE_ERR_UNSUPPORTED;
+    case GEMM_NARROW:
+        if constexpr (!(FP8 && SWIGLU))
+            return launch_shape<typename SF::Narrow>(g, tiles, sched, max_tiles, est_tiles, s);
+        return MOE_ERR_UNSUPPORTED;
+    default:
+        return launch_shape<typename SF::Wide>(g, tiles, sched, max_tiles, est_tiles, s);
     }
-    using Wide = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8>;
-    if constexpr (!(FP8 && SWIGLU)) {
-        using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU, FP8>;
-        const long wide_wgs = (long)est_tiles * ceil_div(g.n_out, Wide::COLS);
-        if (wide_wgs < 2 * GM_CUS) return launch_shape<Narrow>(g, tiles, sched, max_tiles, est_tiles, s);
-    }
-    return launch_shape<Wide>(g, tiles, sched, max_tiles, est_tiles, s);
 }
 
 template <bool SWIGLU, bool FP8>

@@ -94,6 +94,15 @@ int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const vo
 int launch_combine(const moe_config &c, const void *y, const float *w, const int32_t *inv, void *out,
                    hipStream_t s);
 
+// ---- single-launch forward (moe_fused.hip) -----------------------------------------------------
+void set_single_launch(int enable);
+int single_launch_mode(const moe_config &c, int tile_rows);
+int single_launch_timeouts(unsigned *out);
+int launch_fused(const moe_config &c, int tile_rows, int max_tiles, const void *x, const float *router_w,
+                 const float *bias, void *route_ws, int32_t *ids, float *w, int32_t *offsets, int32_t *sorted_pair,
+                 int32_t *inv, moe_tile *tiles, int32_t *sched, const void *w1, const void *w2, void *act, void *y,
+                 void *out, hipStream_t s);
+
 // ---- grouped GEMMs: operand description shared by the host side and the kernel instantiations ----
 constexpr int GM_STEP_BYTES = 128;        // bytes of every row consumed per K step
 
@@ -109,6 +118,64 @@ struct GemmArgs {
     int k_groups;                 // distinct K-loop starting points spread over the workgroups (1 = all start at 0)
     int nt_out;                   // write the output with non-temporal stores (it is too large to stay in L2 anyway)
 };
+
+// Workgroup width of a grouped GEMM launch, from the problem statement alone (est_tiles: tiles a
+// balanced router is expected to produce; the kernels read the real count from device memory).
+//   wide    8 wavefronts, two 16-row weight blocks each: 128 gate/up or 256 down columns per workgroup.
+//   narrow  4 wavefronts (half the columns) when the wide ones would leave compute units without
+//           work; not for the fp8 gate/up GEMM, whose epilogue re-quantises a whole 128-column
+//           block per workgroup.
+//   wide4   down projection of low tiles (32 or 64 rows): four weight blocks per wavefront, 512
+//           columns per workgroup.  Its K loop is short (16 steps for fp8 with I = 2048), so a
+//           workgroup's fixed costs are a third of its life, and the accumulators of a low tile
+//           leave the registers for it (fp8 prefill: down GEMM -4 %).  Not for 16-row tiles, where
+//           two workgroups per compute unit already overlap those costs (decode shape: +0.5 %).
+enum GemmWidth { GEMM_NARROW = 0, GEMM_WIDE = 1, GEMM_WIDE4 = 2 };
+constexpr int kComputeUnits = 256;
+inline GemmWidth gemm_width(int mb_max, bool swiglu, bool fp8, int n_out, int est_tiles)
+{
+    const int wide_cols = swiglu ? 128 : 256;
+    if (!swiglu && (mb_max == 2 || mb_max == 4) && (long)est_tiles * ceil_div(n_out, 512) >= 4 * kComputeUnits)
+        return GEMM_WIDE4;
+    if (!(fp8 && swiglu) && (long)est_tiles * ceil_div(n_out, wide_cols) < 2 * kComputeUnits) return GEMM_NARROW;
+    return GEMM_WIDE;
+}
+// Tiles a balanced router is expected to produce.
+inline int expected_tiles(const moe_config &c)
+{
+    const long pairs = (long)c.T * c.top_k;
+    const int el = local_experts(c);
+    return (int)(pairs < el ? pairs : el);
+}
+
+// Number of distinct K-loop starting points for rows of `row_bytes` bytes: every K step its own
+// when the row stride is a multiple of 4 KiB (measured: such strides lose 10-15% of the stream rate
+// when all workgroups walk K in step; other strides gain nothing and only spread the token rows
+// over more of L2).
+inline int k_groups_for(int row_bytes) { return row_bytes % 4096 == 0 ? row_bytes / GM_STEP_BYTES : 1; }
+
+// An output that does not fit the L2s (8 x 4 MiB) anyway is written with non-temporal stores:
+// cached stores of such a stream push the token rows the workgroups share out of L2 (measured
+// -4..6 % on the gate/up GEMM); a small output stays cached for the kernel that reads it next.
+inline int nt_output(size_t bytes) { return bytes > (size_t)32 << 20 ? 1 : 0; }
+
+inline GemmArgs gateup_args(const moe_config &c, const void *x, const float *x_scale, const void *w1,
+                            const float *w1_scale, const int32_t *sorted_pair, void *act, float *act_scale)
+{
+    const int es = c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
+    return GemmArgs{static_cast<const unsigned char *>(x), x_scale, static_cast<const unsigned char *>(w1), w1_scale,
+                    sorted_pair, static_cast<unsigned char *>(act), act_scale, c.H, c.I, c.top_k,
+                    k_groups_for(c.H * es), nt_output((size_t)c.T * c.top_k * c.I * es)};
+}
+
+inline GemmArgs down_args(const moe_config &c, const void *act, const float *act_scale, const void *w2,
+                          const float *w2_scale, void *y)
+{
+    const int es = c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
+    return GemmArgs{static_cast<const unsigned char *>(act), act_scale, static_cast<const unsigned char *>(w2), w2_scale,
+                    nullptr, static_cast<unsigned char *>(y), nullptr, c.I, c.H, c.top_k,
+                    k_groups_for(c.I * es), nt_output((size_t)c.T * c.top_k * c.H * 2)};
+}
 
 // kernel instantiations per operand type (moe_gemm_{gateup,down}_{bf16,fp8}.hip)
 int launch_gemm_gateup_bf16(int tile_rows, const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,

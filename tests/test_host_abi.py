@@ -133,6 +133,23 @@ def test_static_scratch_entry_refuses_large_problems_without_touching_the_device
     assert int(re.search(r"MOE_STATIC_SCRATCH_BYTES = (\d+) << 20", text).group(1)) << 20 == moe.STATIC_SCRATCH_BYTES
 
 
+def test_single_launch_path_is_a_property_of_the_problem_statement(lib):
+    """Which problems moe_forward runs as one launch once that is switched on (host logic only; the
+    GPU tests compare the paths)."""
+    mode = lambda name: moe.moe_single_launch_mode(moe.MoEConfig.from_workload(syn.WORKLOADS[name]))
+    assert mode("tiny") == moe.SINGLE_LAUNCH_NONE                       # off by default
+    try:
+        moe.moe_single_launch(True)
+        assert mode("tiny") == moe.SINGLE_LAUNCH_ALL
+        for name in ("dsv3_decode", "mixtral_prefill", "dsv3_prefill", "fp8_prefill", "fp8_local32"):
+            assert mode(name) == moe.SINGLE_LAUNCH_NONE
+    finally:
+        moe.moe_single_launch(False)
+    bad = moe.MoEConfig(T=16, H=100, I=128, E=8, top_k=2)
+    assert lib.moe_single_launch_mode(C.byref(bad)) == -2
+    assert lib.moe_single_launch_timeouts(None) == -1
+
+
 def test_quantise_on_the_path_sizes_and_argument_checks(lib):
     wl = syn.WORKLOADS["fp8_prefill"]
     cfg = moe.MoEConfig.from_workload(wl)
