@@ -169,9 +169,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     const int cbyte = ((lane & 7) ^ crow) << 4;               // copy: byte offset of the logical chunk for this lane's slot
     const int rows = tile.rows;
     // Weights are read once and marked non-temporal so they do not push the shared token rows out
-    // of L2.  Exception (measured): the down projection of an expert with several row tiles, whose
-    // workgroups run side by side and share each weight line through L2.
-    const bool share_weights = !SWIGLU && tile.count > 1;
+    // of L2.  Exception (measured): an expert with several row tiles, whose workgroups run side by
+    // side and share each weight line through L2 - in the down projection from two tiles on, in the
+    // gate/up projection from three on (hot experts and the compute-bound regime: -3..5 %; with two
+    // tiles the cacheable weight stream costs the token rows more than the sharing saves: +1..4 %).
+    const bool share_weights = tile.count > (SWIGLU ? 2 : 1);
     const int n_out = g.n_out;
     const size_t row_bytes = (size_t)g.K * ES;
     const int nk = (int)(row_bytes / GM_STEP_BYTES);
