@@ -117,6 +117,16 @@ typedef struct moe_tile {
  * at their ends). */
 enum { MOE_WORK_RANGES = 8, MOE_SCHED_INTS = 16 };
 
+/* Launch shape of a grouped GEMM for this problem (a property of the problem statement alone;
+ * which = 0: gate/up, 1: down), for tests and tuning:
+ *   plan[0] tile rows (= moe_tile_rows)      plan[1] wavefronts per workgroup
+ *   plan[2] 16-row weight blocks per wavefront   plan[3] output columns per workgroup
+ *   plan[4] 1: XCD r works through work range r (whole tiles); 0: eight parts of equal item count
+ *   plan[5] 1: a last round that fills at most half an XCD is handed out as half-width items
+ * Returns MOE_OK or the error code of the problem statement. */
+enum { MOE_GEMM_PLAN_INTS = 8 };
+MOE_API int moe_gemm_plan(const moe_config *cfg, int which, int32_t *plan /* HOST, MOE_GEMM_PLAN_INTS */);
+
 /* Bytes of device scratch moe_route / moe_forward need for this problem. */
 MOE_API size_t moe_route_workspace_size(const moe_config *cfg);
 MOE_API size_t moe_workspace_size(const moe_config *cfg);

@@ -19,7 +19,7 @@ EXPORTS = [
     "moe_tile_rows", "moe_max_tiles", "moe_route_workspace_size", "moe_workspace_size",
     "moe_route", "moe_quantize_act", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm_down",
     "moe_combine", "moe_forward", "moe_forward_marked", "moe_init", "moe_forward_static",
-    "moe_single_launch", "moe_single_launch_mode", "moe_single_launch_timeouts",
+    "moe_single_launch", "moe_single_launch_mode", "moe_single_launch_timeouts", "moe_gemm_plan",
     "moe_error_string", "moe_last_hip_error",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20   # MOE_STATIC_SCRATCH_BYTES
@@ -101,6 +101,8 @@ def load():
     lib.moe_init.argtypes = []
     lib.moe_forward_static.restype = C.c_int
     lib.moe_forward_static.argtypes = [cfgp, vp, f32p, f32p, f32p, vp, f32p, vp, f32p, vp, vp]
+    lib.moe_gemm_plan.restype = C.c_int
+    lib.moe_gemm_plan.argtypes = [cfgp, C.c_int, C.POINTER(C.c_int32)]
     lib.moe_single_launch.restype = None
     lib.moe_single_launch.argtypes = [C.c_int]
     lib.moe_single_launch_mode.restype = C.c_int
@@ -167,6 +169,14 @@ def moe_route_workspace_size(cfg: MoEConfig) -> int:
 
 def moe_workspace_size(cfg: MoEConfig) -> int:
     return int(load().moe_workspace_size(C.byref(cfg)))
+
+
+def moe_gemm_plan(cfg: MoEConfig, which: str) -> dict:
+    """Launch shape of the "gateup" or "down" grouped GEMM for this problem (see include/moe.h)."""
+    plan = (C.c_int32 * 8)()
+    _check(load().moe_gemm_plan(C.byref(cfg), {"gateup": 0, "down": 1}[which], plan), "moe_gemm_plan")
+    return {"tile_rows": plan[0], "wavefronts": plan[1], "blocks_per_wavefront": plan[2], "columns": plan[3],
+            "whole_ranges": bool(plan[4]), "half_items": bool(plan[5])}
 
 
 def _bytes(n: int, device) -> torch.Tensor:

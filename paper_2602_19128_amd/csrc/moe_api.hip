@@ -138,6 +138,26 @@ extern "C" {
 int32_t moe_tile_rows(const moe_config *cfg) { return validate(cfg) == MOE_OK ? tile_rows_for(*cfg) : 0; }
 int32_t moe_max_tiles(const moe_config *cfg) { return validate(cfg) == MOE_OK ? max_tiles_for(*cfg) : 0; }
 
+int moe_gemm_plan(const moe_config *cfg, int which, int32_t *plan)
+{
+    const int rc = validate(cfg);
+    if (rc != MOE_OK) return rc;
+    if (!plan || (which != 0 && which != 1)) return MOE_ERR_INVALID;
+    const bool swiglu = which == 0, f8 = fp8(cfg);
+    const int rows = tile_rows_for(*cfg), est = expected_tiles(*cfg);
+    const GemmWidth wd = gemm_width(rows / 16, swiglu, f8, swiglu ? cfg->I : cfg->H, est);
+    const int waves = wd == GEMM_NARROW ? 4 : 8;
+    const int blocks = wd == GEMM_WIDE4 ? 4 : 2;
+    for (int i = 0; i < MOE_GEMM_PLAN_INTS; ++i) plan[i] = 0;
+    plan[0] = rows;
+    plan[1] = waves;
+    plan[2] = blocks;
+    plan[3] = waves * (swiglu ? 16 : 16 * blocks);
+    plan[4] = est <= 8 * MOE_WORK_RANGES ? 1 : 0;
+    plan[5] = (waves >= 8 && !(f8 && swiglu)) ? 1 : 0;
+    return MOE_OK;
+}
+
 size_t moe_route_workspace_size(const moe_config *cfg)
 {
     return validate(cfg) == MOE_OK ? route_workspace_bytes(router_view(*cfg)) : 0;

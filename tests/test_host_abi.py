@@ -133,6 +133,38 @@ def test_static_scratch_entry_refuses_large_problems_without_touching_the_device
     assert int(re.search(r"MOE_STATIC_SCRATCH_BYTES = (\d+) << 20", text).group(1)) << 20 == moe.STATIC_SCRATCH_BYTES
 
 
+def test_parity_cases_reach_the_kernel_shapes_the_benchmarks_run(lib):
+    """The launch shape of both grouped GEMMs for every benchmark workload, and the small parity
+    cases that are there to reach the same kernel instantiations whole-tile (tests/test_gpu_parity.py)."""
+    import test_gpu_parity as tp
+    plan = lambda wl, which: moe.moe_gemm_plan(moe.MoEConfig.from_workload(wl), which)
+    shape = lambda wl, which: tuple(plan(wl, which)[k] for k in ("tile_rows", "wavefronts", "blocks_per_wavefront"))
+    W = syn.WORKLOADS
+    # benchmark workloads
+    assert shape(W["mixtral_prefill"], "gateup") == (256, 8, 2) and shape(W["mixtral_prefill"], "down") == (256, 4, 2)
+    assert plan(W["mixtral_prefill"], "gateup")["whole_ranges"] and plan(W["mixtral_prefill"], "gateup")["half_items"]
+    for name in ("dsv3_prefill", "dsv3_prefill_skew"):
+        assert shape(W[name], "gateup") == (256, 8, 2) and shape(W[name], "down") == (256, 8, 2)
+        assert not plan(W[name], "gateup")["whole_ranges"]
+    assert shape(W["dsv3_decode"], "gateup") == (16, 8, 2) and shape(W["dsv3_decode"], "down") == (16, 8, 2)
+    assert shape(W["fp8_prefill"], "gateup") == (64, 8, 2) and shape(W["fp8_prefill"], "down") == (64, 8, 4)
+    assert shape(W["fp8_local32"], "gateup") == (256, 8, 2) and shape(W["fp8_local32"], "down") == (256, 8, 2)
+    assert plan(W["fp8_local32"], "gateup")["whole_ranges"]
+    # the small cases that stand in for them
+    C_ = tp.CASES
+    assert shape(C_["wide128_gateup_halves"], "gateup") == (128, 8, 2)
+    g = plan(C_["wide128_gateup_halves"], "gateup")
+    assert g["whole_ranges"] and g["half_items"] and (C_["wide128_gateup_halves"].I // g["columns"]) % 32 in range(1, 17)
+    assert shape(C_["wide256_gateup_split"], "gateup") == (256, 8, 2)       # = Mixtral / DeepSeek-shaped gate/up
+    assert shape(C_["wide256_down_split"], "down") == (256, 8, 2)           # = DeepSeek-shaped down
+    for which in ("gateup", "down"):
+        assert shape(C_["wide256_zigzag"], which) == (256, 8, 2) and not plan(C_["wide256_zigzag"], which)["whole_ranges"]
+    assert shape(C_["ragged128"], "down")[1:] == (4, 2) and shape(C_["fp8_tall"], "down") == (256, 4, 2)    # narrow
+    assert shape(C_["low_tiles"], "down") == (32, 8, 4) and shape(C_["low_tiles_fp8"], "down") == (32, 8, 4)
+    assert shape(C_["fp8_tall"], "gateup") == (256, 8, 2) and shape(C_["fp8_deep_h"], "gateup")[1:] == (8, 2)
+    assert lib.moe_gemm_plan(C.byref(moe.MoEConfig.from_workload(W["tiny"])), 2, (C.c_int32 * 8)()) == -1
+
+
 def test_single_launch_path_is_a_property_of_the_problem_statement(lib):
     """Which problems moe_forward runs as one launch once that is switched on (host logic only; the
     GPU tests compare the paths)."""
