@@ -276,8 +276,10 @@ int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scal
     if (single_launch_mode(*cfg, tr) == MOE_SINGLE_LAUNCH_ALL) {
         rc = launch_fused(*cfg, tr, mt, x, router_w, bias, ws + l.route, ids, w, offsets, sorted_pair, inv, tiles,
                           sched, w1, w2, act, y, out, s);
-        for (int i = 0; rc == MOE_OK && i < 5; ++i) rc = mark();   // the one launch has done all five steps
-        return rc;
+        if (rc != MOE_ERR_UNSUPPORTED) {                      // (a device too small for it takes the pipeline)
+            for (int i = 0; rc == MOE_OK && i < 5; ++i) rc = mark();   // the one launch has done all five steps
+            return rc;
+        }
     }
     const void *x_route = x;                                  // what the router scores
     const float *x_route_scale = x_scale;

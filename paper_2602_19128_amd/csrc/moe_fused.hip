@@ -22,6 +22,8 @@
 // Every phase is the device code of the multi-launch path, instantiated for the kernel shapes that
 // path picks for the same problem, so the results are the same bits.
 //
+// Only every eighth workgroup of the launch takes part (workgroups are handed to the XCDs in turn), so
+// a launch normally sits on one XCD, at most 32 workgroups, and its barriers stay inside one L2.
 // The barriers use a few counters in static device memory (zero between launches: the last
 // workgroup to leave a launch clears them).  A wait is bounded (about two seconds of the constant
 // 100 MHz clock): a workgroup that gives up counts a time-out, goes on, still arrives at every later
@@ -45,12 +47,15 @@ constexpr unsigned long long FZ_WAIT_TICKS = 200000000ull;    // bounded wait: ~
 constexpr int FZ_MAX_PAIRS = 1024;                            // every workgroup sorts all pairs itself
 constexpr int FZ_MAX_EXPERTS = FZ_THREADS;                    // the sort-scatter gives one thread to every local expert
 
+// Barrier counters, each on a cache line of its own.
+struct alignas(128) SyncWord { unsigned v; unsigned pad[31]; };
 struct GridSync {
-    unsigned arrived[FZ_BARRIERS];     // workgroups that reached barrier b of the running launch
-    unsigned departed;                 // workgroups that finished the running launch
-    unsigned timeouts;                 // waits that were given up since the library was loaded
+    SyncWord arrived[FZ_BARRIERS];     // workgroups that reached barrier b of the running launch
+    SyncWord departed;                 // workgroups that finished the running launch
+    SyncWord xcc_mask;                 // bit x: a workgroup of the running launch runs on XCD x
+    SyncWord timeouts;                 // waits that were given up since the library was loaded
 };
-static __device__ GridSync g_sync;     // all zero between launches
+static __device__ GridSync g_sync;     // all zero between launches (except timeouts)
 
 enum RouteMode { ROUTE_FEW = 0, ROUTE_FEW_SPLIT = 1, ROUTE_TILED = 2 };
 
@@ -77,48 +82,82 @@ struct FusedArgs {
     int T, out_H, top_k;
 };
 
-// All workgroups of the launch meet here.  Writes made before the barrier by any thread of any
-// workgroup are visible after it to every thread of every workgroup: the workgroup barrier in front
-// completes every wavefront's stores (they are in this XCD's L2 then), thread 0 writes that L2's
-// dirty lines back and invalidates what the compute unit and the L2 hold of other XCDs' data once
-// for the whole workgroup (one such pair per workgroup instead of one per thread: 30 -> 3 us per barrier).
-__device__ __forceinline__ void grid_barrier(int b, unsigned nblocks)
+__device__ __forceinline__ unsigned xcc_id()
 {
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        __hip_atomic_fetch_add(&g_sync.arrived[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned long long t0 = 0;
-        for (unsigned polls = 0;
-             __hip_atomic_load(&g_sync.arrived[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nblocks; ++polls) {
-            __builtin_amdgcn_s_sleep(1);
-            if ((polls & 63u) == 63u) {                       // look at the clock now and then
-                const unsigned long long now = wall_clock64();
-                if (t0 == 0) t0 = now;
-                if (now - t0 > FZ_WAIT_TICKS) {               // give up: count it, go on, keep arriving
-                    __hip_atomic_fetch_add(&g_sync.timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    }
-    __syncthreads();
+    unsigned v;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(v));
+    return v;
 }
 
-// Last thing a workgroup does: the last one out leaves the counters zeroed for the next launch.
-__device__ __forceinline__ void grid_depart(unsigned nblocks)
+// Read-modify-write that returns the value the L2 held and is complete when it returns (a plain
+// load could be served by the compute unit's own cache; an atomic without a result may still be on
+// its way when the next one is issued).  bits = 0 reads the word.
+__device__ __forceinline__ unsigned or_in_l2(unsigned *p, unsigned bits)
 {
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned before = __hip_atomic_fetch_add(&g_sync.departed, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        if (before == nblocks - 1) {                          // everyone else has passed every barrier and left
-            for (int b = 0; b < FZ_BARRIERS; ++b)
-                __hip_atomic_store(&g_sync.arrived[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&g_sync.departed, 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned old;
+    asm volatile("global_atomic_or %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(old) : "v"(p), "v"(bits) : "memory");
+    return old;
+}
+
+// All workgroups of the launch meet here.  Writes made before the barrier by any thread of any
+// workgroup are visible after it to every thread of every workgroup.
+//
+// The workgroup barrier in front completes every wavefront's stores: they are in this XCD's L2
+// then.  Thread 0 arrives and polls with atomics, then drops what the compute unit's cache (and the
+// L2, of other XCDs' data) holds, once for the whole workgroup.  When the workgroups run on
+// several XCDs, thread 0 first writes its L2's dirty lines back (`spread`); when they all share one
+// XCD - the normal case, see the kernel - they share its L2 and nothing has to be written back.
+// Whether they do is established by the first barrier of a launch, which every workgroup enters
+// after publishing the id of its XCD.  (Measured: cache operations per thread instead of per
+// workgroup 30 us per barrier; per workgroup with the workgroups spread over eight XCDs about 5 us;
+// on one XCD without the write-back 1..2 us including the wait for the slowest workgroup.)
+struct GridBarrier {
+    unsigned nblocks;
+    bool spread;                        // workgroups on more than one XCD; only thread 0's copy is used
+
+    __device__ __forceinline__ void meet(int b, bool first)
+    {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            if (first) (void)or_in_l2(&g_sync.xcc_mask.v, 1u << xcc_id());   // done before this workgroup arrives
+            if (spread) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __hip_atomic_fetch_add(&g_sync.arrived[b].v, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            unsigned long long t0 = 0;
+            for (unsigned polls = 0; or_in_l2(&g_sync.arrived[b].v, 0u) < nblocks; ++polls) {
+                __builtin_amdgcn_s_sleep(1);
+                if ((polls & 63u) == 63u) {                   // look at the clock now and then
+                    const unsigned long long now = wall_clock64();
+                    if (t0 == 0) t0 = now;
+                    if (now - t0 > FZ_WAIT_TICKS) {           // give up: count it, go on, keep arriving
+                        __hip_atomic_fetch_add(&g_sync.timeouts.v, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            if (first) {                                      // every arrival published its bit before arriving
+                const unsigned mask = or_in_l2(&g_sync.xcc_mask.v, 0u);
+                spread = (mask & (mask - 1u)) != 0u;
+            }
+        }
+        __syncthreads();
+    }
+
+    // Last thing a workgroup does: the last one out leaves the counters zeroed for the next launch.
+    __device__ __forceinline__ void depart()
+    {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned before = __hip_atomic_fetch_add(&g_sync.departed.v, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (before == nblocks - 1) {                      // everyone else has passed every barrier and left
+                for (int b = 0; b < FZ_BARRIERS; ++b)
+                    __hip_atomic_store(&g_sync.arrived[b].v, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&g_sync.xcc_mask.v, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&g_sync.departed.v, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
-}
+};
 
 template <int EPL>
 __device__ __forceinline__ void topk_phase(const FusedArgs &a, int block, int nblocks)
@@ -135,7 +174,11 @@ template <int MB_MAX>
 __global__ __launch_bounds__(FZ_THREADS) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int block = (int)blockIdx.x, nblocks = (int)gridDim.x;
+    // Workgroups are handed to the XCDs in turn; only every eighth one takes part, so that the
+    // launch normally sits on one XCD and its barriers stay inside that XCD's L2.
+    if (blockIdx.x % MOE_WORK_RANGES != 0) return;
+    const int block = (int)blockIdx.x / MOE_WORK_RANGES, nblocks = (int)gridDim.x / MOE_WORK_RANGES;
+    GridBarrier sync{(unsigned)nblocks, true};              // (spread until the first barrier has shown otherwise)
     int bar = 0;
 
     // ---- routing ---------------------------------------------------------------------------------
@@ -147,7 +190,7 @@ __global__ __launch_bounds__(FZ_THREADS) void fused_forward_kernel(FusedArgs a)
             router_logits_tile<false>(a.x, nullptr, a.router_w, a.zpart, a.tp.T, a.H, a.tp.E, a.rg.k_per_split,
                                       r % a.rg.tiles_t, r / a.rg.tiles_t, split, lds);
         }
-        grid_barrier(bar++, nblocks);                         // the partial logits of every H slice are there
+        sync.meet(bar, bar == 0), ++bar;                      // the partial logits of every H slice are there
         switch (a.epl) {
         case 1: topk_phase<1>(a, block, nblocks); break;
         case 2: topk_phase<2>(a, block, nblocks); break;
@@ -164,28 +207,30 @@ __global__ __launch_bounds__(FZ_THREADS) void fused_forward_kernel(FusedArgs a)
             for (int b = block; b < ceil_div(a.tp.T, 4); b += nblocks)
                 router_few_tokens<false, 1>(a.x, nullptr, a.router_w, a.bias, a.ids, a.w, a.tp, a.H, b, part_z);
         }
-        ++bar;                                                // (the counter of the logits barrier stays unused)
     }
-    grid_barrier(bar++, nblocks);                             // every token is routed
+    sync.meet(bar, bar == 0), ++bar;                          // every token is routed
 
     // ---- sort-scatter ------------------------------------------------------------------------------
     permute_block<FZ_THREADS>(a.ids, a.P, a.EL, a.e_first, a.tile_rows, a.max_tiles, a.offsets, a.sorted_pair,
                               a.inv, a.tiles, a.sched, reinterpret_cast<int *>(smem), 0, 1);
     {
-        __threadfence();                                      // this workgroup reads back what it has just written
+        // this workgroup reads back what it has just written: its stores are complete after the
+        // workgroup barrier, and one invalidate keeps the compute unit's cache from answering with older lines
+        __syncthreads();
+        if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         __syncthreads();
         // ---- expert GEMMs and combine --------------------------------------------------------------
         using SH1 = typename ShapesFor<MB_MAX, true, false>::Narrow;
         using SH2 = typename ShapesFor<MB_MAX, false, false>::Narrow;
         gemm_items<SH1>(a.g1, a.tiles, a.sched, a.col_tiles1, a.whole_ranges, 32, block, nblocks, smem);
-        grid_barrier(bar++, nblocks);                         // act is complete
+        sync.meet(bar, false), ++bar;                         // act is complete
         gemm_items<SH2>(a.g2, a.tiles, a.sched, a.col_tiles2, a.whole_ranges, 32, block, nblocks, smem);
-        grid_barrier(bar++, nblocks);                         // y is complete
+        sync.meet(bar, false), ++bar;                         // y is complete
         const long long shares = (long long)a.T * (a.out_H / 8);
         for (long long idx = (long long)block * FZ_THREADS + threadIdx.x; idx < shares; idx += (long long)nblocks * FZ_THREADS)
             combine_chunk<false>(reinterpret_cast<const uint16_t *>(a.g2.out), a.w, a.inv, a.out, a.out_H, a.top_k, idx);
     }
-    grid_depart(nblocks);
+    sync.depart();
 }
 
 template <int MB_MAX>
@@ -219,7 +264,7 @@ int launch_variant(const FusedArgs &a, int blocks, int lds, hipStream_t s)
     static DeviceOnce lds_limit_set;
     const int rc = set_dynamic_lds(lds_limit_set, reinterpret_cast<const void *>(kern), lds);
     if (rc != MOE_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(FZ_THREADS), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(blocks * MOE_WORK_RANGES), dim3(FZ_THREADS), lds, s, a);   // one in eight takes part
     return check_launch();
 }
 
@@ -232,7 +277,7 @@ int single_launch_timeouts(unsigned *out)
     GridSync host;
     hipError_t e = hipMemcpyFromSymbol(&host, HIP_SYMBOL(g_sync), sizeof(host), 0, hipMemcpyDeviceToHost);
     if (e != hipSuccess) { set_last_hip_error(e); return MOE_ERR_HIP; }
-    *out = host.timeouts;
+    *out = host.timeouts.v;
     return MOE_OK;
 }
 
@@ -257,7 +302,7 @@ int launch_fused(const moe_config &c, int tile_rows, int max_tiles, const void *
                  void *out, hipStream_t s)
 {
     const int cus = compute_units();
-    if (cus < 8) return MOE_ERR_HIP;
+    if (cus < 8 * MOE_WORK_RANGES) return MOE_ERR_UNSUPPORTED;   // (the caller falls back to the pipeline)
     FusedArgs a{};
     a.x = x; a.router_w = router_w; a.bias = bias;
     a.zpart = static_cast<float *>(route_ws);
@@ -296,8 +341,10 @@ int launch_fused(const moe_config &c, int tile_rows, int max_tiles, const void *
     if (items2 > need) need = items2;
     const long comb = ((long)c.T * (c.H / 8) + FZ_THREADS - 1) / FZ_THREADS;
     if (comb > need) need = comb;
+    // workgroups that take part: a multiple of eight (the GEMM schedule has eight parts), at most
+    // the compute units of one XCD
     int blocks = (int)((need + 7) / 8 * 8);
-    const int cap = cus / 8 * 8;
+    const int cap = cus / MOE_WORK_RANGES / 8 * 8;
     if (blocks > cap) blocks = cap;
     if (blocks < 8) blocks = 8;
     switch (mb) {
