@@ -12,11 +12,13 @@ Shapes follow the MoE operator the paper analyses (Sec. 4.5: DeepSeek-V3 style,
 The paper measured on captured serving traces that are not available; these
 tensors stand in for them.
 
-Every tensor has its own generator stream derived from (seed, tensor id), so a
-tensor's values do not depend on which other tensors were generated, or in what
-order.  Values depend on the device the generator runs on (CPU and GPU use
-different generators); one test or benchmark always hands the *same* tensors to
-the kernels and to the checker.
+Every value is a pure function of (seed, tensor id, element index): a counter-based generator
+(the splitmix64 sequence, keyed per tensor) written with integer tensor operations only, so a
+tensor's values depend neither on which other tensors were generated, nor on the order, nor on the
+device: a draw on the GPU and a draw on the CPU give the same bits, and one device's share of the
+experts holds exactly the values of that slice of the full layer.  Normal variates are the sum of
+twelve 16-bit uniforms (Irwin-Hall: mean 0, variance 1, support +-6), which needs integer additions
+and one exact scaling only; library normal generators differ between devices and math libraries.
 """
 from __future__ import annotations
 
@@ -85,15 +87,76 @@ WORKLOADS: Dict[str, Workload] = {
 # tensor ids for the per-tensor generator streams
 _TID = {"x": 1, "router_w": 2, "bias": 3, "w1": 4, "w2": 5}
 
-
-def _gen(seed: int, tid: int, device) -> torch.Generator:
-    g = torch.Generator(device=device)
-    g.manual_seed(seed * 1_000_003 + tid * 7919 + 12345)
-    return g
+_M64 = (1 << 64) - 1
 
 
-def _normal(shape, std: float, g: torch.Generator, device) -> torch.Tensor:
-    return torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std
+def _s64(v: int) -> int:
+    """A 64-bit pattern as the signed integer torch.int64 holds."""
+    v &= _M64
+    return v - (1 << 64) if v >= (1 << 63) else v
+
+
+_GOLD, _MIX1, _MIX2 = _s64(0x9E3779B97F4A7C15), _s64(0xBF58476D1CE4E5B9), _s64(0x94D049BB133111EB)
+
+
+def _lsr(x: torch.Tensor, s: int) -> torch.Tensor:
+    """Logical shift right of int64 (the >> of a signed tensor is arithmetic)."""
+    return (x >> s) & ((1 << (64 - s)) - 1)
+
+
+def _mix(x: torch.Tensor) -> torch.Tensor:
+    """The output function of splitmix64 (int64 arithmetic wraps, as the generator needs)."""
+    x = (x ^ _lsr(x, 30)) * _MIX1
+    x = (x ^ _lsr(x, 27)) * _MIX2
+    return x ^ _lsr(x, 31)
+
+
+def _mix_int(v: int) -> int:
+    v &= _M64
+    v = ((v ^ (v >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    v = ((v ^ (v >> 27)) * 0x94D049BB133111EB) & _M64
+    return v ^ (v >> 31)
+
+
+def _key(seed: int, tid: int) -> int:
+    """Start state of a tensor's stream."""
+    return _s64(_mix_int(_mix_int(seed * 0x9E3779B97F4A7C15 + 0x1234567) + tid * 0x9E3779B97F4A7C15))
+
+
+def _words(key: int, first: int, count: int, per: int, j: int, device) -> torch.Tensor:
+    """Word j (of `per`) of elements first .. first+count-1: output number per*index + j of the stream."""
+    n = torch.arange(first, first + count, dtype=torch.int64, device=device) * per + (j + 1)
+    return _mix(n * _GOLD + key)
+
+
+_CHUNK = 1 << 25          # elements generated at a time (bounds the int64 temporaries)
+
+
+def _normal(shape, std: float, seed: int, tid: int, device, first: int = 0) -> torch.Tensor:
+    """fp32 tensor of `shape`; element i of the flattened tensor is variate number first + i of stream (seed, tid)."""
+    total = 1
+    for d in shape:
+        total *= d
+    out = torch.empty((total,), dtype=torch.float32, device=device)
+    key = _key(seed, tid)
+    for at in range(0, total, _CHUNK):
+        cnt = min(_CHUNK, total - at)
+        acc = torch.zeros((cnt,), dtype=torch.int64, device=device)
+        for j in range(3):                               # 3 words = 12 uniforms of 16 bits
+            h = _words(key, first + at, cnt, 3, j, device)
+            acc += (h & 0xFFFF) + (_lsr(h, 16) & 0xFFFF) + (_lsr(h, 32) & 0xFFFF) + _lsr(h, 48)
+        # sum of 12 uniforms on {0..65535}: mean 393210, standard deviation 65536 (to 1e-10); both steps exact in fp32
+        out[at:at + cnt] = (acc - 393210).to(torch.float32) * (1.0 / 65536.0)
+    return (out * std).reshape(shape)
+
+
+def _uniform(shape, seed: int, tid: int, device) -> torch.Tensor:
+    """fp32 uniforms on [0, 1) with 24 bits (exact in fp32)."""
+    total = 1
+    for d in shape:
+        total *= d
+    h = _words(_key(seed, tid), 0, total, 1, 0, device)
+    return (_lsr(h, 40).to(torch.float32) * (1.0 / 16777216.0)).reshape(shape)
 
 
 def hot_expert_ids(wl: Workload):
@@ -118,7 +181,8 @@ def quantize_rows_1x128(v: torch.Tensor):
     assert K % QBLOCK == 0
     b = v.reshape(R, K // QBLOCK, QBLOCK)
     amax = b.abs().amax(dim=-1)
-    scale = torch.where(amax > 0, amax / FP8_MAX, torch.ones_like(amax))
+    scale = torch.where(amax > 0, amax / torch.full_like(amax, FP8_MAX), torch.ones_like(amax))   # (a tensor divisor: the
+    # division by a Python scalar is a multiplication by its reciprocal on some devices)
     q = (b / scale.unsqueeze(-1)).clamp_(-FP8_MAX, FP8_MAX).to(torch.float8_e4m3fn)
     return q.reshape(R, K).contiguous(), scale.contiguous()
 
@@ -129,7 +193,8 @@ def quantize_blocks_128x128(v: torch.Tensor):
     assert N % QBLOCK == 0 and K % QBLOCK == 0
     b = v.reshape(N // QBLOCK, QBLOCK, K // QBLOCK, QBLOCK)
     amax = b.abs().amax(dim=(1, 3))
-    scale = torch.where(amax > 0, amax / FP8_MAX, torch.ones_like(amax))
+    scale = torch.where(amax > 0, amax / torch.full_like(amax, FP8_MAX), torch.ones_like(amax))   # (a tensor divisor: the
+    # division by a Python scalar is a multiplication by its reciprocal on some devices)
     q = (b / scale[:, None, :, None]).clamp_(-FP8_MAX, FP8_MAX).to(torch.float8_e4m3fn)
     return q.reshape(N, K).contiguous(), scale.contiguous()
 
@@ -170,18 +235,18 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu",
     hidden ~ N(0,1); router W ~ N(0,1/H) fp32; expert weights ~ N(0,1/fan_in);
     bias ~ U(-0.1,0.1) (+hot_bias on the hot experts).  bf16 workloads round to
     bf16; fp8 workloads block-quantise (1x128 activations, 128x128 weights).
-    Expert weights are drawn one expert at a time to bound the fp32 temporaries; in
-    local-expert mode only the local experts are kept (every expert is still drawn, so a
-    local share holds the same values as the corresponding slice of the full draw).
+    Expert weights are drawn one expert at a time to bound the temporaries; in local-expert
+    mode only the local experts are drawn, and they hold the values of the same experts of
+    the full layer.
     """
     dev = torch.device(device)
     T, H, I, E = wl.T, wl.H, wl.I, wl.E
-    x32 = _normal((T, H), 1.0, _gen(seed, _TID["x"], dev), dev)
-    router_w = _normal((E, H), H ** -0.5, _gen(seed, _TID["router_w"], dev), dev)
+    x32 = _normal((T, H), 1.0, seed, _TID["x"], dev)
+    router_w = _normal((E, H), H ** -0.5, seed, _TID["router_w"], dev)
     bias = None
     if wl.has_bias:
-        gb = _gen(seed, _TID["bias"], dev)
-        bias = (torch.rand((E,), generator=gb, device=dev, dtype=torch.float32) * 0.2 - 0.1)
+        bias = _uniform((E,), seed, _TID["bias"], dev) * 0.2
+        bias = bias - 0.1
         hot = hot_expert_ids(wl)
         if hot:
             bias[torch.tensor(hot, device=dev)] += wl.hot_bias
@@ -202,17 +267,14 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu",
     if wl.fp8:
         w1_scale = torch.empty((EL, 2 * I // QBLOCK, H // QBLOCK), dtype=torch.float32, device=dev)
         w2_scale = torch.empty((EL, H // QBLOCK, I // QBLOCK), dtype=torch.float32, device=dev)
-    g1 = _gen(seed, _TID["w1"], dev)
-    g2 = _gen(seed, _TID["w2"], dev)
-    for e in range(lo + EL):
-        a = _normal((2 * I, H), H ** -0.5, g1, dev)
-        b = _normal((H, I), I ** -0.5, g2, dev)
-        if e >= lo:
-            if wl.fp8:
-                w1[e - lo], w1_scale[e - lo] = quantize_blocks_128x128(a)
-                w2[e - lo], w2_scale[e - lo] = quantize_blocks_128x128(b)
-            else:
-                w1[e - lo] = a.to(torch.bfloat16)
-                w2[e - lo] = b.to(torch.bfloat16)
+    for e in range(lo, lo + EL):                         # expert e's values are those of the full layer's expert e
+        a = _normal((2 * I, H), H ** -0.5, seed, _TID["w1"], dev, first=e * 2 * I * H)
+        b = _normal((H, I), I ** -0.5, seed, _TID["w2"], dev, first=e * H * I)
+        if wl.fp8:
+            w1[e - lo], w1_scale[e - lo] = quantize_blocks_128x128(a)
+            w2[e - lo], w2_scale[e - lo] = quantize_blocks_128x128(b)
+        else:
+            w1[e - lo] = a.to(torch.bfloat16)
+            w2[e - lo] = b.to(torch.bfloat16)
         del a, b
     return MoEInputs(wl, x, router_w, bias, w1, w2, x_scale, w1_scale, w2_scale)

@@ -28,7 +28,7 @@ def main():
     offsets, sorted_pair, inv = orc.permute(ids, p.E)
     doc = {
         "workload": "tiny", "seed": 0,
-        "source": "oracle/moe_oracle.c on paper_2602_19128_amd.synthetic inputs (CPU generator)",
+        "source": "oracle/moe_oracle.c on paper_2602_19128_amd.synthetic inputs (counter-based generator, the same bits on every device)",
         "ids": ids.tolist(),
         "w": [[float(f"{v:.12e}") for v in row] for row in w],
         "min_margin": float(margin.min()),
@@ -49,7 +49,7 @@ def main():
     q, scale = orc.quantize_rows_1x128(inp.x)
     qdoc = {
         "workload": "tiny", "seed": 0,
-        "source": "oracle_quantize_rows_1x128 on paper_2602_19128_amd.synthetic hidden states (CPU generator)",
+        "source": "oracle_quantize_rows_1x128 on paper_2602_19128_amd.synthetic hidden states (counter-based generator)",
         "scale_bits": scale.view(np.uint32).reshape(-1).tolist(),
         "codes_row0_block0": q[0, :128].tolist(),
         "code_sum": int(q.astype(np.int64).sum()),
