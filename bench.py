@@ -278,23 +278,26 @@ def measure(wl, inp, host, K, W, cpu_seconds, graph, seed, log, min_warm_ms=0.0)
 
 
 def compact(rec):
-    """The nested form of a workload's record: the same measurements, fewer words."""
+    """The nested form of a workload's record: the same measurements in fewer bytes (the whole
+    line should stay a few KB).  step_us = [route, sort-scatter, gate/up GEMM, down GEMM, combine];
+    gemm_hbm_frac = [gate/up, down] algorithmic bytes / launch time / 8 TB/s; parity = [tokens
+    compared, tie-excused tokens, max |err| / max |ref|, sum |err| / sum |ref|, within tolerance]."""
     r = rec["roofline"]
     c = rec["config"]
-    out = {"us": rec["value"], "unmarked_us": rec["unmarked_us"], "roofline_us": rec["roofline_time_us"], "frac_of_roofline": rec["frac_of_roofline"],
+    out = {"us": rec["value"], "unmarked_us": rec["unmarked_us"], "frac_of_roofline": rec["frac_of_roofline"],
            "dtype": rec["dtype"], "T": c["T"], "pairs": c["routed_pairs"], "active_experts": c["active_experts"],
            "load_max_over_mean": c["max_over_mean_load"], "tflops": rec["tflops"], "frac_mfma": rec["frac_mfma_peak"],
-           "gbps": rec["gbps"], "frac_hbm": rec["frac_hbm_peak"], "step_us": rec["step_us"],
-           "gate_up": {"gbps": r["achieved"], "frac": r["frac"]},
-           "down": {"gbps": r["down_gemm"]["achieved"], "frac": r["down_gemm"]["frac"]}}
+           "gbps": rec["gbps"], "frac_hbm": rec["frac_hbm_peak"],
+           "step_us": [rec["step_us"][k] for k in ("route", "permute", "gemm_swiglu", "gemm_down", "combine")],
+           "gemm_hbm_frac": [r["frac"], r["down_gemm"]["frac"]]}
     if rec["single_launch_us"] is not None:
         out["single_launch_us"] = rec["single_launch_us"]
     if rec["cpu_baseline"]:
         out["cpu_oracle_us"] = rec["cpu_baseline"]["value"]
-        out["cpu_sample"] = rec["cpu_baseline"]["sample"].split(" (")[0] + (" (sampled)" if "sampled" in rec["cpu_baseline"]["sample"] else " (all)")
+        out["cpu_sample"] = rec["cpu_baseline"]["sample"].split(" tokens")[0].replace(" of ", "/") + \
+            (" sampled" if "sampled" in rec["cpu_baseline"]["sample"] else " all")
         p = rec["parity_sample"]
-        out["parity"] = {"tokens": p["tokens"], "tie_excused": p["tie_excused"], "max_rel": float(f"{p['max_rel']:.3g}"),
-                         "mean_rel": float(f"{p['mean_rel']:.3g}"), "ok": p["ok"]}
+        out["parity"] = [p["tokens"], p["tie_excused"], float(f"{p['max_rel']:.3g}"), float(f"{p['mean_rel']:.3g}"), p["ok"]]
     return out
 
 
