@@ -129,7 +129,7 @@ def _words(key: int, first: int, count: int, per: int, j: int, device) -> torch.
     return _mix(n * _GOLD + key)
 
 
-_CHUNK = 1 << 25          # elements generated at a time (bounds the int64 temporaries)
+_CHUNK = 1 << 27          # elements generated at a time (bounds the int64 temporaries: about 1 GiB each)
 
 
 def _normal(shape, std: float, seed: int, tid: int, device, first: int = 0) -> torch.Tensor:
@@ -267,14 +267,21 @@ def make_inputs(wl: Workload, seed: int = 0, device="cpu",
     if wl.fp8:
         w1_scale = torch.empty((EL, 2 * I // QBLOCK, H // QBLOCK), dtype=torch.float32, device=dev)
         w2_scale = torch.empty((EL, H // QBLOCK, I // QBLOCK), dtype=torch.float32, device=dev)
-    for e in range(lo, lo + EL):                         # expert e's values are those of the full layer's expert e
-        a = _normal((2 * I, H), H ** -0.5, seed, _TID["w1"], dev, first=e * 2 * I * H)
-        b = _normal((H, I), I ** -0.5, seed, _TID["w2"], dev, first=e * H * I)
-        if wl.fp8:
-            w1[e - lo], w1_scale[e - lo] = quantize_blocks_128x128(a)
-            w2[e - lo], w2_scale[e - lo] = quantize_blocks_128x128(b)
-        else:
-            w1[e - lo] = a.to(torch.bfloat16)
-            w2[e - lo] = b.to(torch.bfloat16)
-        del a, b
+    def draw(out, out_scale, rows, cols, std, tid):
+        """Experts lo .. lo+EL-1 of the full layer's [E, rows, cols] tensor, several experts at a time."""
+        per = rows * cols
+        group = max(1, _CHUNK // per)
+        for e0 in range(0, EL, group):
+            n = min(group, EL - e0)
+            v = _normal((n * rows, cols), std, seed, tid, dev, first=(lo + e0) * per)
+            if wl.fp8:                                   # rows is a multiple of 128: blocks never straddle experts
+                q, sc = quantize_blocks_128x128(v)
+                out[e0:e0 + n] = q.view(n, rows, cols)
+                out_scale[e0:e0 + n] = sc.view(n, rows // QBLOCK, cols // QBLOCK)
+            else:
+                out[e0:e0 + n] = v.to(torch.bfloat16).view(n, rows, cols)
+            del v
+
+    draw(w1, w1_scale, 2 * I, H, H ** -0.5, _TID["w1"])
+    draw(w2, w2_scale, H, I, I ** -0.5, _TID["w2"])
     return MoEInputs(wl, x, router_w, bias, w1, w2, x_scale, w1_scale, w2_scale)
