@@ -141,11 +141,26 @@ struct Shape {
     static_assert(!(FP8 && SWIGLU) || COLS == kQBlock, "fp8 gate/up: a workgroup re-quantises one 1x128 block per row");
 };
 
+// One item of a launch's work: a row tile, a column slab of it (half: 0 the whole slab, 1 / 2 its
+// first / second half) and the item's number in the launch (which fixes its K rotation).
+struct Item {
+    moe_tile tile;
+    int ct, half, work;
+};
+
 // Everything after the (tile, column slab) decision, instantiated per active row-block count NB.
+// A workgroup may work through several items in a row.  `next` (if has_next) is the item it takes
+// after this one: when both are whole-slab items and the staged output tile of this one leaves the
+// weight ring alone, the first weight stages of `next` are requested before this item's epilogue,
+// so that the latency of their trip from HBM passes while the output is written; the call then
+// returns true and the next call is told so (`prefetched`: its weight copies of stages 0..DW-1
+// are already under way).
 template <class SH, int NB, bool HALF>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &tile, int ct, int half, int work,
-                                          unsigned char *smem)
+__device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, const Item next, const bool has_next,
+                                          const bool prefetched, unsigned char *smem)
 {
+    const moe_tile &tile = item.tile;
+    const int ct = item.ct, half = item.half, work = item.work;
     constexpr int NW = SH::NW, DA = SH::DA, DW = SH::DW;
     constexpr bool SWIGLU = SH::SWIGLU, FP8 = SH::FP8;
     constexpr int ES = FP8 ? 1 : 2;                           // bytes per element
@@ -194,20 +209,24 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
     const int col0 = ct * SH::COLS + half_col + (HALF ? wave % (NW / 2) : wave) * SLAB;   // first output column of this wavefront
     const int wc = active ? GM_W_COPIES : 0;                  // weight copies this wavefront issues per step
     const int w_rows = SWIGLU ? 2 * n_out : n_out;
-    const unsigned char *wbase = g.W + (size_t)tile.expert * w_rows * row_bytes + cbyte;
-    const unsigned char *w_ptr[GM_W_COPIES];
+    // pointers of this wavefront's weight copies for the slab starting at output column c0 of expert e
+    auto weight_ptrs = [&](int e, int c0, const unsigned char *(&ptr)[GM_W_COPIES]) __attribute__((always_inline)) {
+        const unsigned char *wbase = g.W + (size_t)e * w_rows * row_bytes + cbyte;
 #pragma unroll
-    for (int q = 0; q < GM_W_COPIES; ++q) {
-        const int in_blk = (q & 1) * 8 + crow;                // row inside the 16-row block
-        int wrow;
-        if constexpr (SWIGLU) {
-            const int c = min(col0 + in_blk, n_out - 1);      // clamp: columns past the end are never stored
-            wrow = (q < 2) ? c : n_out + c;                   // gate row / matching up row
-        } else {
-            wrow = min(col0 + q * 8 + crow, n_out - 1);
+        for (int q = 0; q < GM_W_COPIES; ++q) {
+            const int in_blk = (q & 1) * 8 + crow;            // row inside the 16-row block
+            int wrow;
+            if constexpr (SWIGLU) {
+                const int c = min(c0 + in_blk, n_out - 1);    // clamp: columns past the end are never stored
+                wrow = (q < 2) ? c : n_out + c;               // gate row / matching up row
+            } else {
+                wrow = min(c0 + q * 8 + crow, n_out - 1);
+            }
+            ptr[q] = wbase + (size_t)wrow * row_bytes;
         }
-        w_ptr[q] = wbase + (size_t)wrow * row_bytes;
-    }
+    };
+    const unsigned char *w_ptr[GM_W_COPIES];
+    weight_ptrs(tile.expert, col0, w_ptr);
     unsigned char *const w_ring = smem + SH::A_RING_BYTES + wave * (SW * GM_W_STAGE);
     unsigned char *const sc_ring = smem + SH::A_RING_BYTES + SH::W_RING_BYTES;
     const uint32_t smem_lds = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
@@ -275,25 +294,29 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
                 copy4_to_lds(sc_ptr + ks_, sc_lds + ((s) % SA) * SH::SC_STAGE_BYTES + wave * 256);     \
         }                                                                                              \
     }
-#define MOE_COPY_WEIGHTS(s)                                                                            \
+#define MOE_COPY_WEIGHTS_OF(s, ptr_, koff_, share_)                                                   \
     {                                                                                                  \
-        const int k0_ = k_rot(s) * GM_STEP_BYTES;                                                      \
+        const int r_ = (s) + (koff_);                                                                  \
+        const int k0_ = (r_ >= nk ? r_ - nk : r_) * GM_STEP_BYTES;                                     \
         const uint32_t dst_ = w_lds + ((s) % SW) * GM_W_STAGE;                                         \
-        if (share_weights) {                                                                           \
+        if (share_) {                                                                                  \
             _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                    \
-                copy16_to_lds<false>(w_ptr[q] + k0_, dst_ + q * 1024);                                 \
+                copy16_to_lds<false>(ptr_[q] + k0_, dst_ + q * 1024);                                  \
         } else {                                                                                       \
             _Pragma("unroll") for (int q = 0; q < GM_W_COPIES; ++q)                                    \
-                copy16_to_lds<true>(w_ptr[q] + k0_, dst_ + q * 1024);                                  \
+                copy16_to_lds<true>(ptr_[q] + k0_, dst_ + q * 1024);                                   \
         }                                                                                              \
     }
+#define MOE_COPY_WEIGHTS(s) MOE_COPY_WEIGHTS_OF(s, w_ptr, koff, share_weights)
 
     // Issue slot t (t = -DW .. nk-1) holds [token copy of step t+DA, weight copy of step t+DW].
     // prologue: slots -DW .. -1
+    // (prefetched: the weight copies of these slots were issued by the previous item of this workgroup,
+    // ahead of all the token copies below)
 #pragma unroll
     for (int t = -DW; t < 0; ++t) {
         if (t + DA >= 0 && t + DA < nk) MOE_COPY_TOKENS(t + DA)
-        if (active && t + DW < nk) MOE_COPY_WEIGHTS(t + DW)
+        if (!prefetched && active && t + DW < nk) MOE_COPY_WEIGHTS(t + DW)
     }
 
     for (int s = 0; s < nk; ++s) {
@@ -306,7 +329,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
 #pragma unroll
         for (int t = 1 - DA; t < 0; ++t)
             in_flight += (s + t + DA < nk ? a_cnt : 0) + (s + t + DW < nk ? wc : 0);
-        wait_vmcnt_upto(in_flight);
+        // (a prefetched item issued its weight copies first and its token copies last, behind the
+        // stores of the previous epilogue: its first step simply waits for all of them)
+        if (prefetched && s == 0) MOE_WAIT_VMCNT(0);
+        else wait_vmcnt_upto(in_flight);
         asm volatile("s_barrier" ::: "memory");               // token stage s complete for everyone; stage s-1 free
         if (s + DA < nk) MOE_COPY_TOKENS(s + DA)
         __builtin_amdgcn_sched_barrier(0);
@@ -411,9 +437,27 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
         }   // active
         __builtin_amdgcn_sched_barrier(0);
     }
-    MOE_WAIT_VMCNT(0);                                        // nothing is in flight any more; cheap insurance for the LDS reuse below
+    // Every copy of this item has landed (the last step waited for its own, and nothing was issued
+    // after those).  The output tile is staged over the token ring; when it stays clear of the
+    // weight ring, this wavefront's first weight stages of the next item go out now.
+    constexpr int STAGED_BYTES = ((SWIGLU && FP8) ? NW * NB * 16 * 4 : 0) + NB * 16 * SH::COLS * ((SWIGLU && FP8) ? 1 : 2);
+    bool gave_next = false;
+    if constexpr (!HALF && STAGED_BYTES <= SH::A_RING_BYTES) {
+        if (has_next && next.half == 0) {
+            const unsigned char *nw_ptr[GM_W_COPIES];
+            weight_ptrs(next.tile.expert, next.ct * SH::COLS + wave * SLAB, nw_ptr);
+            const int nkoff = (int)((long)(next.work % g.k_groups) * nk / g.k_groups);
+            const bool nshare = next.tile.count > (SWIGLU ? 2 : 1);
+#pragma unroll
+            for (int t = 0; t < DW; ++t)
+                if (t < nk) MOE_COPY_WEIGHTS_OF(t, nw_ptr, nkoff, nshare)
+            gave_next = true;
+        }
+    }
+    if (!gave_next) MOE_WAIT_VMCNT(0);                        // nothing is in flight any more; cheap insurance for the LDS reuse below
 #undef MOE_COPY_TOKENS
 #undef MOE_COPY_WEIGHTS
+#undef MOE_COPY_WEIGHTS_OF
 
     // ---- epilogue: lane l holds, for token l%16 of each row block, output columns 4*(l/16)..+3
     // of each of its two weight blocks.  Written straight from that layout a store instruction
@@ -507,25 +551,26 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const moe_tile &til
             else *dst = v;
         }
     }
+    return gave_next;
 }
 
 template <class SH, int NB>
-__device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const moe_tile &tile, int ct, int half,
-                                                int work, unsigned char *smem)
+__device__ __forceinline__ bool dispatch_blocks(int nb, const GemmArgs &g, const Item item, const Item next,
+                                                const bool has_next, const bool prefetched, unsigned char *smem)
 {
     if constexpr (NB > SH::MB_MAX) {
-        return;
+        return false;
     } else {
         constexpr int NEXT = NB + 1;
         if (nb <= NB) {
             if constexpr (SH::HALF_ITEMS) {
-                if (half) gemm_tile<SH, NB, true>(g, tile, ct, half, work, smem);
-                else gemm_tile<SH, NB, false>(g, tile, ct, half, work, smem);
+                if (item.half) return gemm_tile<SH, NB, true>(g, item, next, has_next, prefetched, smem);
+                return gemm_tile<SH, NB, false>(g, item, next, has_next, prefetched, smem);
             } else {
-                gemm_tile<SH, NB, false>(g, tile, ct, half, work, smem);
+                return gemm_tile<SH, NB, false>(g, item, next, has_next, prefetched, smem);
             }
         } else {
-            dispatch_blocks<SH, NEXT>(nb, g, tile, ct, half, work, smem);
+            return dispatch_blocks<SH, NEXT>(nb, g, item, next, has_next, prefetched, smem);
         }
     }
 }
@@ -544,10 +589,16 @@ __device__ __forceinline__ void dispatch_blocks(int nb, const GemmArgs &g, const
 // work than its share of the grid.
 // Workgroup `block` of `nblocks` (a multiple of MOE_WORK_RANGES) works through its share of the
 // schedule; the stand-alone kernel below and the single-launch forward both run this loop.
+// Where a workgroup does take several items (the single-launch forward, whose grid is small), every item
+// but its first has its first weight stages requested before the epilogue of its predecessor (see
+// gemm_tile).  Shrinking the stand-alone launch to make every workgroup loop was measured and is not
+// done: with 2 / 4 / 8 items per workgroup the gate/up GEMM of a 4096-token DeepSeek-shaped prefill took
+// +2 / +8 / +21 % (the hardware's hand-out of fresh workgroups balances tiles of unequal height, a fixed
+// share per workgroup does not), with or without the prefetch.
 template <class SH>
 __device__ __forceinline__ void gemm_items(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
-                                           int col_tiles, int whole_ranges, int round_slots, int block, int nblocks,
-                                           unsigned char *smem)
+                                           int col_tiles, int whole_ranges, int round_slots, int block,
+                                           int nblocks, unsigned char *smem)
 {
     const int part = block % MOE_WORK_RANGES;
     int first, items;
@@ -575,31 +626,49 @@ __device__ __forceinline__ void gemm_items(const GemmArgs &g, const moe_tile *ti
     const int rest = items % round_slots;
     const int halved = (SH::HALF_ITEMS && whole_ranges && rest > 0 && 2 * rest <= round_slots) ? rest : 0;
     const int slots = zigzag ? nchunks * col_tiles : items + halved;
-    for (int slot = block / MOE_WORK_RANGES; slot < slots; slot += stride) {
+    // the item in slot `slot` of this part (false: the slot is past the end, or a hole of the last, short chunk)
+    auto item_at = [&](int slot, Item &it) __attribute__((always_inline)) -> bool {
+        if (slot >= slots) return false;
         int pos = slot;
         if (zigzag) {
             const int c = slot / col_tiles;
             const int pc = (c & 1) ? nchunks - 1 - (c >> 1) : (c >> 1);
             pos = pc * col_tiles + slot % col_tiles;
-            if (pos >= items) continue;                        // the part's last chunk may be short
+            if (pos >= items) return false;
         }
-        int half = 0;
+        it.half = 0;
         if (pos >= items - halved) {                           // (never together with zigzag)
             const int h = pos - (items - halved);
             pos = items - halved + (h >> 1);
-            half = 1 + (h & 1);
+            it.half = 1 + (h & 1);
         }
-        const int work = first + pos;
-        const moe_tile head = tiles[work / col_tiles];
-        const int local = work - head.first * col_tiles;       // index inside this expert's work
-        const int ct = local / head.count;                     // column slab
-        const moe_tile tile = tiles[head.first + local % head.count];
-        const int nb = ceil_div(tile.rows, 16);
-        dispatch_blocks<SH, 1>(nb, g, tile, ct, half, work, smem);
-        __syncthreads();                                       // the output tile has left LDS
+        it.work = first + pos;
+        const moe_tile head = tiles[it.work / col_tiles];
+        const int local = it.work - head.first * col_tiles;    // index inside this expert's work
+        it.ct = local / head.count;                            // column slab
+        it.tile = tiles[head.first + local % head.count];
+        return true;
+    };
+    // The workgroup takes slots b, b + stride, b + 2 stride, ... (neighbouring workgroups are on
+    // neighbouring slots at any time, so the column slabs of a tile still run side by side and share
+    // its token rows through L2; a workgroup that took consecutive slots instead measured +10..15 %).
+    Item cur{}, nxt{};
+    int slot = block / MOE_WORK_RANGES;
+    bool have = item_at(slot, cur), prefetched = false;
+    while (slot < slots) {
+        const bool have_next = item_at(slot + stride, nxt);
+        if (have) {
+            const int nb = ceil_div(cur.tile.rows, 16);
+            prefetched = dispatch_blocks<SH, 1>(nb, g, cur, nxt, have_next, prefetched, smem);
+            __syncthreads();                                   // the output tile has left LDS
+        } else {
+            prefetched = false;
+        }
+        cur = nxt;
+        have = have_next;
+        slot += stride;
     }
 }
-
 
 template <class SH>
 __global__ __launch_bounds__(SH::THREADS) void grouped_gemm_kernel(GemmArgs g, const moe_tile *__restrict__ tiles,
@@ -625,9 +694,11 @@ int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched,
     if (rc != MOE_OK) return rc;
     // a part holds about an eighth of the tiles; the slack (a tile's slabs, and the half-width items
     // of a last round) keeps the loop in the kernel at one trip
-    const int blocks = ((ceil_div(max_tiles, GM_XCDS) + 1) * col_tiles + (SH::HALF_ITEMS ? round_slots / 2 : 0)) * GM_XCDS;
+    const int part_slots = (ceil_div(max_tiles, GM_XCDS) + 1) * col_tiles + (SH::HALF_ITEMS ? round_slots / 2 : 0);
+    const int blocks = part_slots * GM_XCDS;
     const int whole_ranges = est_tiles <= 8 * GM_XCDS ? 1 : 0;   // at most eight tiles per XCD
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, sched, col_tiles, whole_ranges, round_slots);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(SH::THREADS), SH::LDS_BYTES, s, g, tiles, sched, col_tiles, whole_ranges,
+                       round_slots);
     return check_launch();
 }
 
