@@ -123,6 +123,12 @@ enum { MOE_WORK_RANGES = 8, MOE_SCHED_INTS = 16 };
  *   plan[2] 16-row weight blocks per wavefront   plan[3] output columns per workgroup
  *   plan[4] 1: XCD r works through work range r (whole tiles); 0: eight parts of equal item count
  *   plan[5] 1: a last round that fills at most half an XCD is handed out as half-width items
+ *   plan[6] down projection inside moe_forward: 1, or 2 = K is cut in halves with items of their own
+ *           (few experts with tall tiles and a long K, bf16): the halves' fp32 partial sums take the
+ *           place of y in the workspace and the combine adds them, first half first, before it rounds a
+ *           row to bf16.  moe_grouped_gemm_down itself always reduces over the whole of K (plan[1..5]
+ *           with which = 1 describe what moe_forward launches), so for such a problem the two differ in
+ *           the order of the fp32 sum, both inside the stated tolerance.
  * Returns MOE_OK or the error code of the problem statement. */
 enum { MOE_GEMM_PLAN_INTS = 8 };
 MOE_API int moe_gemm_plan(const moe_config *cfg, int which, int32_t *plan /* HOST, MOE_GEMM_PLAN_INTS */);

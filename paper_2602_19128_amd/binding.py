@@ -176,7 +176,7 @@ def moe_gemm_plan(cfg: MoEConfig, which: str) -> dict:
     plan = (C.c_int32 * 8)()
     _check(load().moe_gemm_plan(C.byref(cfg), {"gateup": 0, "down": 1}[which], plan), "moe_gemm_plan")
     return {"tile_rows": plan[0], "wavefronts": plan[1], "blocks_per_wavefront": plan[2], "columns": plan[3],
-            "whole_ranges": bool(plan[4]), "half_items": bool(plan[5])}
+            "whole_ranges": bool(plan[4]), "half_items": bool(plan[5]), "k_split": plan[6]}
 
 
 def _bytes(n: int, device) -> torch.Tensor:

@@ -94,7 +94,7 @@ Layout layout_for(const moe_config &c)
     l.sched = take(MOE_SCHED_INTS * sizeof(int32_t));
     l.act = take(P * c.I * act_elem);
     l.act_scale = take(c.dtype == MOE_DTYPE_FP8_E4M3 ? P * (c.I / kQBlock) * sizeof(float) : 0);
-    l.y = take(P * c.H * 2);
+    l.y = take(P * c.H * (down_k_split(c, tile_rows_for(c)) > 1 ? 2 * sizeof(float) : 2));   // bf16 rows, or two fp32 partial sums
     l.xq = take(c.quantize_x ? (size_t)c.T * c.H : 0);
     l.xq_scale = take(c.quantize_x ? (size_t)c.T * (c.H / kQBlock) * sizeof(float) : 0);
     l.total = off;
@@ -145,7 +145,8 @@ int moe_gemm_plan(const moe_config *cfg, int which, int32_t *plan)
     if (!plan || (which != 0 && which != 1)) return MOE_ERR_INVALID;
     const bool swiglu = which == 0, f8 = fp8(cfg);
     const int rows = tile_rows_for(*cfg), est = expected_tiles(*cfg);
-    const GemmWidth wd = gemm_width(rows / 16, swiglu, f8, swiglu ? cfg->I : cfg->H, est);
+    const int ks = swiglu ? 1 : down_k_split(*cfg, rows);
+    const GemmWidth wd = ks > 1 ? GEMM_WIDE : gemm_width(rows / 16, swiglu, f8, swiglu ? cfg->I : cfg->H, est);
     const int waves = wd == GEMM_NARROW ? 4 : 8;
     const int blocks = wd == GEMM_WIDE4 ? 4 : 2;
     for (int i = 0; i < MOE_GEMM_PLAN_INTS; ++i) plan[i] = 0;
@@ -154,7 +155,8 @@ int moe_gemm_plan(const moe_config *cfg, int which, int32_t *plan)
     plan[2] = blocks;
     plan[3] = waves * (swiglu ? 16 : 16 * blocks);
     plan[4] = est <= 8 * MOE_WORK_RANGES ? 1 : 0;
-    plan[5] = (waves >= 8 && !(f8 && swiglu)) ? 1 : 0;
+    plan[5] = (waves >= 8 && !(f8 && swiglu) && ks == 1) ? 1 : 0;
+    plan[6] = ks;
     return MOE_OK;
 }
 
@@ -223,7 +225,7 @@ int moe_grouped_gemm_down(const moe_config *cfg, const void *act, const float *a
     if (cfg->T == 0) return MOE_OK;
     if (!act || !w2 || !tiles || !sched || !y_out) return MOE_ERR_INVALID;
     if (fp8(cfg) && (!act_scale || !w2_scale)) return MOE_ERR_INVALID;
-    return launch_gemm_down(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), act, act_scale, w2, w2_scale, tiles,
+    return launch_gemm_down(*cfg, tile_rows_for(*cfg), max_tiles_for(*cfg), 1, act, act_scale, w2, w2_scale, tiles,
                             sched, y_out, (hipStream_t)stream);
 }
 
@@ -298,9 +300,10 @@ int moe_forward_marked(const moe_config *cfg, const void *x, const float *x_scal
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
     rc = launch_gemm_swiglu(*cfg, tr, mt, x, x_scale, w1, w1_scale, sorted_pair, tiles, sched, act, act_scale, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
-    rc = launch_gemm_down(*cfg, tr, mt, act, act_scale, w2, w2_scale, tiles, sched, y, s);
+    const int ks = down_k_split(*cfg, tr);
+    rc = launch_gemm_down(*cfg, tr, mt, ks, act, act_scale, w2, w2_scale, tiles, sched, y, s);
     if (rc != MOE_OK || (rc = mark()) != MOE_OK) return rc;
-    rc = launch_combine(*cfg, y, w, inv, out, s);
+    rc = launch_combine(*cfg, y, w, inv, out, s, ks);
     if (rc != MOE_OK) return rc;
     return mark();
 }

@@ -7,6 +7,9 @@
 // larger than the L2s and was streamed out by the down projection (4096 DeepSeek tokens: 103 ->
 // 80 us); wrong when only a share of the experts is local and the few rows that exist are still
 // cached (measured 24 -> 29 us on a 32-of-256 share), so the launch picks.
+// SPLIT: the expert rows arrive as the two fp32 partial sums of a down projection whose K was cut in
+// halves (y = [2][P,H] floats): a row is their sum, first half first, rounded to bf16 as the unsplit
+// projection rounds its output, and then enters the weighted sum as above.
 #pragma once
 #include "moe_internal.hpp"
 
@@ -15,10 +18,10 @@ namespace {
 
 // One thread's share: 8 consecutive hidden elements of one token; idx numbers the shares token-major
 // (idx < T * H / 8).
-template <bool NT>
+template <bool NT, bool SPLIT = false>
 __device__ __forceinline__ void combine_chunk(const uint16_t *__restrict__ y, const float *__restrict__ w,
                                               const int32_t *__restrict__ inv, uint16_t *__restrict__ out, int H,
-                                              int k, long long idx)
+                                              int k, long long idx, size_t split_stride = 0)
 {
     const int chunks = H / 8;
     const int t = (int)(idx / chunks), h = (int)(idx % chunks) * 8;
@@ -26,7 +29,7 @@ __device__ __forceinline__ void combine_chunk(const uint16_t *__restrict__ y, co
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
     // slots in groups of CB: the rows of a group are requested together, then added in slot order
-    constexpr int CB = 8;
+    constexpr int CB = SPLIT ? 2 : 8;
     for (int j0 = 0; j0 < k; j0 += CB) {
         int row[CB];
         float wt[CB];
@@ -42,7 +45,20 @@ __device__ __forceinline__ void combine_chunk(const uint16_t *__restrict__ y, co
         {
             typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
             u32x4_t v = {0u, 0u, 0u, 0u};
-            if (row[u] >= 0) {
+            if constexpr (SPLIT) {
+                typedef float f32x4_t __attribute__((ext_vector_type(4)));
+                if (row[u] >= 0) {
+                    const float *p0 = reinterpret_cast<const float *>(y) + (size_t)row[u] * H + h;
+                    const float *p1 = reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(y) + split_stride) +
+                                      (size_t)row[u] * H + h;
+                    const f32x4_t a0 = *reinterpret_cast<const f32x4_t *>(p0), a1 = *reinterpret_cast<const f32x4_t *>(p0 + 4);
+                    const f32x4_t b0 = *reinterpret_cast<const f32x4_t *>(p1), b1 = *reinterpret_cast<const f32x4_t *>(p1 + 4);
+                    v[0] = pack_bf16x2(a0[0] + b0[0], a0[1] + b0[1]);
+                    v[1] = pack_bf16x2(a0[2] + b0[2], a0[3] + b0[3]);
+                    v[2] = pack_bf16x2(a1[0] + b1[0], a1[1] + b1[1]);
+                    v[3] = pack_bf16x2(a1[2] + b1[2], a1[3] + b1[3]);
+                }
+            } else if (row[u] >= 0) {
                 const u32x4_t *src = reinterpret_cast<const u32x4_t *>(y + (size_t)row[u] * H + h);
                 v = NT ? __builtin_nontemporal_load(src) : *src;
             }

@@ -329,7 +329,7 @@ int launch_fused(const moe_config &c, int tile_rows, int max_tiles, const void *
     const int lds_front = (int)sizeof(LogitsLds) > (int)(sizeof(int) * permute_lds_ints(FZ_THREADS, a.EL))
                               ? (int)sizeof(LogitsLds) : (int)(sizeof(int) * permute_lds_ints(FZ_THREADS, a.EL));
     a.g1 = gateup_args(c, x, nullptr, w1, nullptr, sorted_pair, act, nullptr);
-    a.g2 = down_args(c, act, nullptr, w2, nullptr, y);
+    a.g2 = down_args(c, act, nullptr, w2, nullptr, y, 1);   // (tiles of at most 64 rows: K is never split here)
     a.whole_ranges = expected_tiles(c) <= 8 * MOE_WORK_RANGES ? 1 : 0;
     const int mb = tile_rows / 16;
     const int cols1 = 16 * 4, cols2 = 32 * 4;                 // columns per narrow workgroup (gate/up, down)

@@ -16,11 +16,11 @@ int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const 
     return launch_gemm_gateup_bf16(tile_rows, g, tiles, sched, max_tiles, expected_tiles(c), s);
 }
 
-int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const void *act, const float *act_scale,
-                     const void *w2, const float *w2_scale, const moe_tile *tiles, const int32_t *sched, void *y,
-                     hipStream_t s)
+int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, int k_split, const void *act,
+                     const float *act_scale, const void *w2, const float *w2_scale, const moe_tile *tiles,
+                     const int32_t *sched, void *y, hipStream_t s)
 {
-    const GemmArgs g = down_args(c, act, act_scale, w2, w2_scale, y);
+    const GemmArgs g = down_args(c, act, act_scale, w2, w2_scale, y, k_split);
     if (c.dtype == MOE_DTYPE_FP8_E4M3)
         return launch_gemm_down_fp8(tile_rows, g, tiles, sched, max_tiles, expected_tiles(c), s);
     return launch_gemm_down_bf16(tile_rows, g, tiles, sched, max_tiles, expected_tiles(c), s);

@@ -117,10 +117,13 @@ __device__ __forceinline__ int lds_off(int row, int chunk)   // byte offset of l
 // Compile-time shape of one kernel variant.
 //   MB_MAX  row blocks (of 16) a tile may have        NW  wavefronts per workgroup
 //   DA      token-row stages in flight                DW  weight stages in flight (DW >= DA)
-template <int MB_MAX_, int NW_, int DA_, int DW_, bool SWIGLU_, bool FP8_, int BPW_ = 2>
+//   SPLITK  down projection whose K is cut in halves (see down_k_split): an item is (tile, column slab, half
+//           of K) and leaves an fp32 partial sum
+template <int MB_MAX_, int NW_, int DA_, int DW_, bool SWIGLU_, bool FP8_, int BPW_ = 2, bool SPLITK_ = false>
 struct Shape {
     static constexpr int MB_MAX = MB_MAX_, NW = NW_, DA = DA_, DW = DW_;
-    static constexpr bool SWIGLU = SWIGLU_, FP8 = FP8_;
+    static constexpr bool SWIGLU = SWIGLU_, FP8 = FP8_, SPLITK = SPLITK_;
+    static_assert(!SPLITK || (!SWIGLU && !FP8), "K is split for the bf16 down projection only");
     static constexpr int BPW = BPW_;                          // 16-row weight blocks per wavefront (gate/up: one gate + one up block)
     static_assert(!SWIGLU || BPW == 2, "gate/up: one gate and one up block per wavefront");
     static constexpr int THREADS = NW * kWave;
@@ -137,7 +140,7 @@ struct Shape {
     static_assert(DW >= DA && DA >= 1, "weights are copied at least as far ahead as token rows");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
     // half-width items (see gemm_tile): wide workgroups only; the fp8 gate/up epilogue needs whole 128-column blocks
-    static constexpr bool HALF_ITEMS = NW >= 8 && !(FP8 && SWIGLU);
+    static constexpr bool HALF_ITEMS = NW >= 8 && !(FP8 && SWIGLU) && !SPLITK;
     static_assert(!(FP8 && SWIGLU) || COLS == kQBlock, "fp8 gate/up: a workgroup re-quantises one 1x128 block per row");
 };
 
@@ -160,7 +163,9 @@ __device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, co
                                           const bool prefetched, unsigned char *smem)
 {
     const moe_tile &tile = item.tile;
-    const int ct = item.ct, half = item.half, work = item.work;
+    // (split K: the items of one column slab are its halves of K, first half first)
+    const int ct = SH::SPLITK ? item.ct >> 1 : item.ct, kh = SH::SPLITK ? item.ct & 1 : 0;
+    const int half = item.half, work = item.work;
     constexpr int NW = SH::NW, DA = SH::DA, DW = SH::DW;
     constexpr bool SWIGLU = SH::SWIGLU, FP8 = SH::FP8;
     constexpr int ES = FP8 ? 1 : 2;                           // bytes per element
@@ -191,7 +196,8 @@ __device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, co
     const bool share_weights = tile.count > (SWIGLU ? 2 : 1);
     const int n_out = g.n_out;
     const size_t row_bytes = (size_t)g.K * ES;
-    const int nk = (int)(row_bytes / GM_STEP_BYTES);
+    const int nk = (int)(row_bytes / GM_STEP_BYTES) / (SH::SPLITK ? 2 : 1);   // K steps of this item
+    const size_t kbase = (size_t)kh * nk * GM_STEP_BYTES;     // byte offset of its first step in a row
     // Workgroups that run side by side start their K loops at different columns (and wrap around):
     // with every workgroup at the same column, rows whose stride is a multiple of a large power of
     // two keep hitting the same memory channels.  The sum over K is the same set of terms.
@@ -211,7 +217,7 @@ __device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, co
     const int w_rows = SWIGLU ? 2 * n_out : n_out;
     // pointers of this wavefront's weight copies for the slab starting at output column c0 of expert e
     auto weight_ptrs = [&](int e, int c0, const unsigned char *(&ptr)[GM_W_COPIES]) __attribute__((always_inline)) {
-        const unsigned char *wbase = g.W + (size_t)e * w_rows * row_bytes + cbyte;
+        const unsigned char *wbase = g.W + (size_t)e * w_rows * row_bytes + kbase + cbyte;
 #pragma unroll
         for (int q = 0; q < GM_W_COPIES; ++q) {
             const int in_blk = (q & 1) * 8 + crow;            // row inside the 16-row block
@@ -257,7 +263,7 @@ __device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, co
         size_t src;
         if constexpr (SWIGLU) src = (size_t)(g.sorted_pair[tile.row0 + r] / g.top_k);
         else src = (size_t)(tile.row0 + r);
-        a_ptr[i] = g.A + src * row_bytes + cbyte;
+        a_ptr[i] = g.A + src * row_bytes + kbase + cbyte;
         a_dst[i] = p * 1024;
     }
     // fp8: wavefront j also copies the activation scales of rows 64j..64j+63 (4 bytes per lane)
@@ -442,7 +448,7 @@ __device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, co
     // weight ring, this wavefront's first weight stages of the next item go out now.
     constexpr int STAGED_BYTES = ((SWIGLU && FP8) ? NW * NB * 16 * 4 : 0) + NB * 16 * SH::COLS * ((SWIGLU && FP8) ? 1 : 2);
     bool gave_next = false;
-    if constexpr (!HALF && STAGED_BYTES <= SH::A_RING_BYTES) {
+    if constexpr (!HALF && !SH::SPLITK && STAGED_BYTES <= SH::A_RING_BYTES) {
         if (has_next && next.half == 0) {
             const unsigned char *nw_ptr[GM_W_COPIES];
             weight_ptrs(next.tile.expert, next.ct * SH::COLS + wave * SLAB, nw_ptr);
@@ -458,6 +464,48 @@ __device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, co
 #undef MOE_COPY_TOKENS
 #undef MOE_COPY_WEIGHTS
 #undef MOE_COPY_WEIGHTS_OF
+
+    if constexpr (SH::SPLITK) {
+        // ---- epilogue of a K half: the fp32 accumulators leave as they are, to this half's partial-sum
+        // array.  Staged through LDS like the bf16 tile below (a lane holds 4 consecutive columns of 16
+        // rows: written straight from registers a store would touch 16 rows x 16 bytes); a 1 KiB row per
+        // token does not fit for a whole tall tile, so the tile leaves in parts of NBP row blocks.
+        constexpr int ROW_B = SH::COLS * 4;
+        constexpr int CPR = ROW_B / 16;
+        constexpr int PARTS = (NB * 16 * ROW_B + SH::LDS_BYTES - 1) / SH::LDS_BYTES;
+        constexpr int NBP = (NB + PARTS - 1) / PARTS;
+        static_assert(NBP * 16 * ROW_B <= SH::LDS_BYTES, "a part of the output tile must fit the LDS of the rings");
+        auto stage_at = [&](int r, int byte) __attribute__((always_inline)) {
+            return smem + r * ROW_B + ((((byte >> 4) ^ ((r & (CPR / 2 - 1)) << 1))) << 4) + (byte & 15);
+        };
+        unsigned char *const part_out = g.out + (size_t)kh * g.split_stride;
+        const size_t out_pitch = (size_t)n_out * 4;
+#pragma unroll
+        for (int part = 0; part < PARTS; ++part) {
+            const int m0 = part * NBP;                        // first row block of this part
+            __syncthreads();                                  // the rings (or the previous part) are done with
+#pragma unroll
+            for (int m = m0; m < m0 + NBP && m < NB; ++m) {
+                const int r = (m - m0) * 16 + l16;
+#pragma unroll
+                for (int b = 0; b < BPW; ++b)
+                    *reinterpret_cast<f32x4 *>(stage_at(r, (wave * SLAB + b * 16 + lq * 4) * 4)) = acc[m][b];
+            }
+            __syncthreads();
+            const int part_rows = min(rows - m0 * 16, NBP * 16);
+            for (int c = tid; c < part_rows * CPR; c += SH::THREADS) {
+                const int r = c / CPR, ch = c % CPR;
+                const int col = ct * SH::COLS + ch * 4;       // n_out is a multiple of 16 elements: chunks are all in or all out
+                if (col < n_out) {
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(stage_at(r, ch * 16));
+                    u32x4 *dst = reinterpret_cast<u32x4 *>(part_out + (size_t)(tile.row0 + m0 * 16 + r) * out_pitch + (size_t)col * 4);
+                    if (g.nt_out) __builtin_nontemporal_store(v, dst);
+                    else *dst = v;
+                }
+            }
+        }
+        return false;
+    } else {
 
     // ---- epilogue: lane l holds, for token l%16 of each row block, output columns 4*(l/16)..+3
     // of each of its two weight blocks.  Written straight from that layout a store instruction
@@ -552,6 +600,7 @@ __device__ __forceinline__ bool gemm_tile(const GemmArgs &g, const Item item, co
         }
     }
     return gave_next;
+    }   // not SPLITK
 }
 
 template <class SH, int NB>
@@ -683,7 +732,7 @@ template <class SH>
 int launch_shape(const GemmArgs &g, const moe_tile *tiles, const int32_t *sched, int max_tiles, int est_tiles,
                  hipStream_t s)
 {
-    const int col_tiles = ceil_div(g.n_out, SH::COLS);
+    const int col_tiles = ceil_div(g.n_out, SH::COLS) * (SH::SPLITK ? 2 : 1);   // split K: two items per column slab
     auto kern = grouped_gemm_kernel<SH>;
     // workgroups one XCD runs at once: LDS (160 KiB) and wavefront slots (32) of a compute unit decide it
     int per_cu = (160 * 1024) / SH::LDS_BYTES;
@@ -710,6 +759,7 @@ struct ShapesFor {
     using Wide = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8>;
     using Narrow = Shape<MB_MAX, 4, DA, 3, SWIGLU, FP8>;
     using Wide4 = Shape<MB_MAX, 8, DA, DW, SWIGLU, FP8, SWIGLU ? 2 : 4>;
+    using WideSplit = Shape<MB_MAX, 8, DA, DW, false, false, 2, true>;
 };
 
 template <int MB_MAX, bool SWIGLU, bool FP8>
@@ -717,6 +767,11 @@ int launch_for_rows(const GemmArgs &g, const moe_tile *tiles, const int32_t *sch
                     hipStream_t s)
 {
     using SF = ShapesFor<MB_MAX, SWIGLU, FP8>;
+    if (g.k_split > 1) {                                      // (down_k_split asks for it only where this holds)
+        if constexpr (!SWIGLU && !FP8 && MB_MAX >= 8)
+            return launch_shape<typename SF::WideSplit>(g, tiles, sched, max_tiles, est_tiles, s);
+        return MOE_ERR_UNSUPPORTED;
+    }
     switch (gemm_width(MB_MAX, SWIGLU, FP8, g.n_out, est_tiles)) {
     case GEMM_WIDE4:
         if constexpr (!SWIGLU && (MB_MAX == 2 || MB_MAX == 4))

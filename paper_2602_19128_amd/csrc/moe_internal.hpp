@@ -88,11 +88,13 @@ int launch_gemm_swiglu(const moe_config &c, int tile_rows, int max_tiles, const 
                        const float *x_scale, const void *w1, const float *w1_scale,
                        const int32_t *sorted_pair, const moe_tile *tiles, const int32_t *sched,
                        void *act, float *act_scale, hipStream_t s);
-int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, const void *act,
+// (k_split: see down_k_split; y then receives the partial sums)
+int launch_gemm_down(const moe_config &c, int tile_rows, int max_tiles, int k_split, const void *act,
                      const float *act_scale, const void *w2, const float *w2_scale,
                      const moe_tile *tiles, const int32_t *sched, void *y, hipStream_t s);
+// (k_split = 2: y holds the fp32 partial sums of a K-split down projection, [2][P,H])
 int launch_combine(const moe_config &c, const void *y, const float *w, const int32_t *inv, void *out,
-                   hipStream_t s);
+                   hipStream_t s, int k_split = 1);
 
 // ---- single-launch forward (moe_fused.hip) -----------------------------------------------------
 void set_single_launch(int enable);
@@ -117,6 +119,9 @@ struct GemmArgs {
     int K, n_out, top_k;
     int k_groups;                 // distinct K-loop starting points spread over the workgroups (1 = all start at 0)
     int nt_out;                   // write the output with non-temporal stores (it is too large to stay in L2 anyway)
+    int k_split;                  // down only: 1, or 2 = K is cut in halves, each with items of its own, and `out`
+                                  // holds the halves' fp32 partial sums, [2][P,n_out], split_stride bytes apart
+    size_t split_stride;
 };
 
 // Workgroup width of a grouped GEMM launch, from the problem statement alone (est_tiles: tiles a
@@ -148,6 +153,21 @@ inline int expected_tiles(const moe_config &c)
     return (int)(pairs < el ? pairs : el);
 }
 
+// Down projection of a layer with few experts and tall tiles (Mixtral-shaped prefill): the narrow
+// workgroups such a launch would take own 128 output columns each and pull more token bytes than
+// weight bytes through the compute unit's memory pipeline, which then runs at its own limit (about
+// 50 GB/s) instead of the chip's.  Cutting K in two instead gives as many items of 256 columns: half
+// the token bytes per weight byte (measured 192 -> 163 us at 512 Mixtral tokens).  The halves' fp32
+// partial sums go to the workspace and the combine adds them, first half first, before it rounds a
+// row to bf16, so the result has one fixed order.  bf16 only; the K loop must stay long.
+inline int down_k_split(const moe_config &c, int tile_rows)
+{
+    if (c.dtype != MOE_DTYPE_BF16 || tile_rows < 128) return 1;
+    if (gemm_width(tile_rows / 16, false, false, c.H, expected_tiles(c)) != GEMM_NARROW) return 1;
+    const int nk = c.I * 2 / 128;                            // K steps of the whole reduction
+    return (nk >= 64 && nk % 2 == 0) ? 2 : 1;
+}
+
 // Number of distinct K-loop starting points for rows of `row_bytes` bytes: every K step its own
 // when the row stride is a multiple of 4 KiB (measured: such strides lose 10-15% of the stream rate
 // when all workgroups walk K in step; other strides gain nothing and only spread the token rows
@@ -165,16 +185,18 @@ inline GemmArgs gateup_args(const moe_config &c, const void *x, const float *x_s
     const int es = c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
     return GemmArgs{static_cast<const unsigned char *>(x), x_scale, static_cast<const unsigned char *>(w1), w1_scale,
                     sorted_pair, static_cast<unsigned char *>(act), act_scale, c.H, c.I, c.top_k,
-                    k_groups_for(c.H * es), nt_output((size_t)c.T * c.top_k * c.I * es)};
+                    k_groups_for(c.H * es), nt_output((size_t)c.T * c.top_k * c.I * es), 1, 0};
 }
 
+// y: the bf16 output [P,H]; with k_split = 2 the fp32 partial sums [2][P,H] instead.
 inline GemmArgs down_args(const moe_config &c, const void *act, const float *act_scale, const void *w2,
-                          const float *w2_scale, void *y)
+                          const float *w2_scale, void *y, int k_split)
 {
     const int es = c.dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
+    const size_t out_bytes = (size_t)c.T * c.top_k * c.H * (k_split > 1 ? 4 : 2);
     return GemmArgs{static_cast<const unsigned char *>(act), act_scale, static_cast<const unsigned char *>(w2), w2_scale,
                     nullptr, static_cast<unsigned char *>(y), nullptr, c.I, c.H, c.top_k,
-                    k_groups_for(c.I * es), nt_output((size_t)c.T * c.top_k * c.H * 2)};
+                    k_groups_for(c.I * es), nt_output(out_bytes * k_split), k_split, out_bytes};
 }
 
 // kernel instantiations per operand type (moe_gemm_{gateup,down}_{bf16,fp8}.hip)

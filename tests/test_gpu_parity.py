@@ -75,6 +75,9 @@ CASES = {
     "wide256_gateup_split": syn.Workload("wide256_gateup_split", T=700, H=128, I=16384, E=4, top_k=2),
     #   down projection, 256-row tiles, every expert cut into two tiles (which share their weights through L2)
     "wide256_down_split": syn.Workload("wide256_down_split", T=700, H=32768, I=128, E=4, top_k=2),
+    #   few experts, tall tiles and a long K: inside the forward the down projection cuts K in halves (fp32
+    #   partial sums, added by the combine); 2.5 column slabs of 256, ragged tiles, an odd step count per half
+    "down_k_halves": syn.Workload("down_k_halves", T=300, H=640, I=4224, E=4, top_k=2),
     #   more than 64 tiles of up to 16 row blocks: both GEMMs wide, work cut into equal parts and
     #   walked alternating between tall and short tiles
     "wide256_zigzag": syn.Workload("wide256_zigzag", T=2800, H=1024, I=512, E=128, top_k=8),

@@ -141,7 +141,13 @@ def test_parity_cases_reach_the_kernel_shapes_the_benchmarks_run(lib):
     shape = lambda wl, which: tuple(plan(wl, which)[k] for k in ("tile_rows", "wavefronts", "blocks_per_wavefront"))
     W = syn.WORKLOADS
     # benchmark workloads
-    assert shape(W["mixtral_prefill"], "gateup") == (256, 8, 2) and shape(W["mixtral_prefill"], "down") == (256, 4, 2)
+    assert shape(W["mixtral_prefill"], "gateup") == (256, 8, 2) and shape(W["mixtral_prefill"], "down") == (256, 8, 2)
+    # few experts, tall tiles, long K: the forward's down projection cuts K in halves; its workspace holds both partial sums
+    assert plan(W["mixtral_prefill"], "down")["k_split"] == 2 and not plan(W["mixtral_prefill"], "down")["half_items"]
+    mix = W["mixtral_prefill"]
+    assert moe.moe_workspace_size(moe.MoEConfig.from_workload(mix)) >= mix.T * mix.top_k * mix.H * 8
+    for name in W:
+        assert plan(W[name], "gateup")["k_split"] == 1 and (name == "mixtral_prefill" or plan(W[name], "down")["k_split"] == 1)
     assert plan(W["mixtral_prefill"], "gateup")["whole_ranges"] and plan(W["mixtral_prefill"], "gateup")["half_items"]
     for name in ("dsv3_prefill", "dsv3_prefill_skew"):
         assert shape(W[name], "gateup") == (256, 8, 2) and shape(W[name], "down") == (256, 8, 2)
@@ -160,6 +166,9 @@ def test_parity_cases_reach_the_kernel_shapes_the_benchmarks_run(lib):
     for which in ("gateup", "down"):
         assert shape(C_["wide256_zigzag"], which) == (256, 8, 2) and not plan(C_["wide256_zigzag"], which)["whole_ranges"]
     assert shape(C_["ragged128"], "down")[1:] == (4, 2) and shape(C_["fp8_tall"], "down") == (256, 4, 2)    # narrow
+    assert plan(C_["ragged128"], "down")["k_split"] == 1 and plan(C_["fp8_tall"], "down")["k_split"] == 1
+    for name in ("down_k_halves", "wide256_gateup_split", "wide128_gateup_halves"):    # K in halves, 8 wavefronts
+        assert plan(C_[name], "down")["k_split"] == 2 and shape(C_[name], "down")[1:] == (8, 2)
     assert shape(C_["low_tiles"], "down") == (32, 8, 4) and shape(C_["low_tiles_fp8"], "down") == (32, 8, 4)
     assert shape(C_["fp8_tall"], "gateup") == (256, 8, 2) and shape(C_["fp8_deep_h"], "gateup")[1:] == (8, 2)
     assert lib.moe_gemm_plan(C.byref(moe.MoEConfig.from_workload(W["tiny"])), 2, (C.c_int32 * 8)()) == -1
