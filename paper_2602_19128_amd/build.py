@@ -1,9 +1,12 @@
 """Builds the HIP library in-tree: paper_2602_19128_amd/libmoe_gfx950.so.
 
-    python -m paper_2602_19128_amd.build
+    python -m paper_2602_19128_amd.build            # the library and the streaming probe
+    python -m paper_2602_19128_amd.build --probe    # the streaming probe only
 
 Every csrc/*.hip file is one translation unit; they are compiled side by side and linked
 into one shared object that exports the C ABI of include/moe.h and nothing else.
+probe/stream_probe.hip is a stand-alone program (the chip's streaming-read rate with the
+grouped GEMMs' access pattern); nothing in the library, the tests or the benchmark needs it.
 """
 from __future__ import annotations
 
@@ -19,6 +22,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoe_gfx950.so")
+PROBE_SRC = os.path.join(PKG, "probe", "stream_probe.hip")
+PROBE = os.path.join(PKG, "probe", "stream_probe")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -46,6 +51,14 @@ def _run(cmd, verbose):
         raise RuntimeError(f"hipcc failed ({res.returncode}): {' '.join(cmd)}\n{err}")
 
 
+def build_probe(verbose: bool = True) -> str:
+    """Compile the stand-alone streaming probe for gfx950."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-fvisibility=hidden")]
+    _run([hipcc, *flags, "-o", PROBE, PROBE_SRC], verbose)
+    return PROBE
+
+
 def build(verbose: bool = True, jobs: int = 0) -> str:
     """Compile every HIP source for gfx950 and link the shared library (always rebuilds)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -63,8 +76,9 @@ def build(verbose: bool = True, jobs: int = 0) -> str:
         _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], verbose)
     finally:
         shutil.rmtree(tmp, ignore_errors=True)
+    build_probe(verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build())
+    print(build_probe() if "--probe" in sys.argv[1:] else build())
