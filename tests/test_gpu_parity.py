@@ -332,3 +332,49 @@ def test_permute_many_pairs_over_several_workgroups(T, k, E, lo, n):
     inv_g = inv.cpu().numpy()
     assert (inv_g[~keep] == -1).all() and np.array_equal(inv_g[keep], inv_r)
     check_tiles(tiles, sched, off_r, moe.moe_tile_rows(cfg))
+
+
+def test_forward_with_k_in_halves_agrees_with_the_staged_steps_and_replays_from_a_graph():
+    """Inside the forward the down projection of `down_k_halves` cuts K in two and the combine adds the
+    partial sums; the stand-alone steps reduce over the whole of K.  The two differ only in the order of
+    the fp32 sum: almost every output element has the same bits, the rest are a bf16 rounding apart.
+    The forward's five launches, captured once, replay to the eager bits."""
+    wl = CASES["down_k_halves"]
+    gpu = syn.make_inputs(wl, seed=3, device="cuda")
+    cfg = moe.MoEConfig.from_workload(wl)
+    assert moe.moe_gemm_plan(cfg, "down")["k_split"] == 2
+    ws = torch.empty((moe.moe_workspace_size(cfg),), dtype=torch.uint8, device="cuda")
+    out = torch.empty((wl.T, wl.H), dtype=torch.bfloat16, device="cuda")
+    moe.forward_inputs(gpu, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    # the same layer step by step
+    ids, w = moe.moe_route(cfg, gpu.x, gpu.x_scale, gpu.router_w, gpu.bias)
+    off, sp, inv, tiles, sched = moe.moe_permute(cfg, ids)
+    act, act_scale = moe.moe_grouped_gemm_swiglu(cfg, gpu.x, gpu.x_scale, gpu.w1, gpu.w1_scale, sp, tiles, sched)
+    y = moe.moe_grouped_gemm_down(cfg, act, act_scale, gpu.w2, gpu.w2_scale, tiles, sched)
+    staged = moe.moe_combine(cfg, y, w, inv)
+    torch.cuda.synchronize()
+    a, b = f64(eager), f64(staged)
+    same = (eager.view(torch.int16) == staged.view(torch.int16)).float().mean().item()
+    print(f"  forward (K in halves) vs staged steps: {same:.4f} of the elements bit-equal, max diff {np.abs(a - b).max():.3e}")
+    assert same > 0.9
+    assert (np.abs(a - b) <= np.abs(b) * 2.0 ** -6 + np.abs(b).max() * 2.0 ** -7).all()
+    # graph replay, with eager work between the replays
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        moe.forward_inputs(gpu, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        moe.forward_inputs(gpu, out=out, workspace=ws)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs"
+        moe.forward_inputs(gpu, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16))
